@@ -1,0 +1,159 @@
+"""CPU oracle for transposable N:M mask finding.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper around ``tsenor_oracle.c`` (plain C, double precision, the
+paper's Algorithm 1 and Algorithm 2 step by step) plus the exact checkers in
+``oracle.exact``.  Only tests, the smoke check and the benchmark's cpu_baseline
+leg may import this package; it shares nothing with the HIP path and never
+imports it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_DIR = Path(__file__).resolve().parent
+_SRC = _DIR / "tsenor_oracle.c"
+_LIB = _DIR / "libtsenor_oracle.so"
+
+TAU_ABSOLUTE = 0
+TAU_REL_MATRIX_MAX = 1
+
+
+def build(force: bool = False) -> Path:
+    """Compile the C oracle with gcc (-O2, no fast-math, OpenMP over blocks)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".so.tmp{os.getpid()}")
+        subprocess.run(
+            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", str(tmp), str(_SRC), "-lm"],
+            check=True,
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(str(_LIB))
+        i64, dbl, i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_int
+        p = ctypes.c_void_p
+        lib.tsenor_oracle_importance.argtypes = [p, i64, i64, i64, p, p]
+        lib.tsenor_oracle_importance.restype = i32
+        lib.tsenor_oracle_tau_eff.argtypes = [p, i64, i64, dbl, i32]
+        lib.tsenor_oracle_tau_eff.restype = dbl
+        lib.tsenor_oracle_dykstra.argtypes = [p, i64, i64, i32, i32, dbl, i32, i32, p, p]
+        lib.tsenor_oracle_dykstra.restype = i32
+        lib.tsenor_oracle_round.argtypes = [p, p, i64, i64, i32, i32, i32, i32, p, p]
+        lib.tsenor_oracle_round.restype = i32
+        lib.tsenor_oracle_swap_scores.argtypes = [p, p, i32, i32, i32, p]
+        lib.tsenor_oracle_swap_scores.restype = i32
+        lib.tsenor_oracle_mask.argtypes = [p, i64, i64, i64, p, i32, i32, dbl, i32, i32, i32, i32, i32, p, p, p, p]
+        lib.tsenor_oracle_mask.restype = i32
+        lib.tsenor_oracle_num_threads.restype = i32
+        lib.tsenor_oracle_set_threads.argtypes = [i32]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def num_threads() -> int:
+    return int(_load().tsenor_oracle_num_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().tsenor_oracle_set_threads(int(n))
+
+
+def importance(W, col_scale=None) -> np.ndarray:
+    """imp = |W| (times col_scale[j]) as one float32 multiply per weight."""
+    W = _f32(W)
+    cs = None if col_scale is None else _f32(col_scale)
+    out = np.empty_like(W)
+    rc = _load().tsenor_oracle_importance(_ptr(W), W.shape[0], W.shape[1], W.shape[1], _ptr(cs), _ptr(out))
+    if rc:
+        raise ValueError(f"tsenor_oracle_importance failed: {rc}")
+    return out
+
+
+def tau_eff(imp, tau: float, tau_mode: int = TAU_ABSOLUTE) -> float:
+    imp = _f32(imp)
+    return float(_load().tsenor_oracle_tau_eff(_ptr(imp), imp.shape[0], imp.shape[1], float(tau), int(tau_mode)))
+
+
+def dykstra(imp, N: int, M: int, tau_eff_value: float, T: int, cols_first: bool = False, return_log_Q: bool = False):
+    """Algorithm 1 on every MxM block of ``imp``; returns log S^(T) (and log Q^(T))."""
+    imp = _f32(imp)
+    rows, cols = imp.shape
+    log_S = np.empty((rows, cols), dtype=np.float64)
+    log_Q = np.empty((rows, cols), dtype=np.float64) if return_log_Q else None
+    rc = _load().tsenor_oracle_dykstra(_ptr(imp), rows, cols, N, M, float(tau_eff_value), T, int(cols_first),
+                                       _ptr(log_S), _ptr(log_Q))
+    if rc:
+        raise ValueError(f"tsenor_oracle_dykstra failed: {rc}")
+    return (log_S, log_Q) if return_log_Q else log_S
+
+
+def round_plan(key, imp, N: int, M: int, L: int = 10, strict_paper: bool = False):
+    """Algorithm 2 on every block: greedy on ``key`` then local search scored on ``imp``.
+
+    Returns (mask uint8, stats[4] = missing-after-greedy, non-positive swaps applied,
+    blocks needing more than L rounds, units still missing at return)."""
+    key = np.ascontiguousarray(key, dtype=np.float64)
+    imp = _f32(imp)
+    rows, cols = imp.shape
+    mask = np.empty((rows, cols), dtype=np.uint8)
+    stats = np.zeros(4, dtype=np.int64)
+    rc = _load().tsenor_oracle_round(_ptr(key), _ptr(imp), rows, cols, N, M, L, int(strict_paper), _ptr(mask),
+                                     _ptr(stats))
+    if rc:
+        raise ValueError(f"tsenor_oracle_round failed: {rc}")
+    return mask, stats
+
+
+def swap_scores(imp_block, S_block, i: int, j: int) -> np.ndarray:
+    """Eq. (5) score matrix of one block for deficient row i and column j (0-based)."""
+    imp_block = _f32(imp_block)
+    S_block = np.ascontiguousarray(S_block, dtype=np.uint8)
+    M = imp_block.shape[0]
+    out = np.empty((M, M), dtype=np.float64)
+    rc = _load().tsenor_oracle_swap_scores(_ptr(imp_block), _ptr(S_block), M, i, j, _ptr(out))
+    if rc:
+        raise ValueError(f"tsenor_oracle_swap_scores failed: {rc}")
+    return out
+
+
+def mask(W, N: int, M: int, tau: float, T: int, *, col_scale=None, tau_mode: int = TAU_ABSOLUTE, L: int = 10,
+         strict_paper: bool = False, cols_first: bool = False, return_plan: bool = False):
+    """The whole path on a float32 matrix W.  Returns dict(mask, stats, tau_eff[, log_S])."""
+    W = _f32(W)
+    rows, cols = W.shape
+    cs = None if col_scale is None else _f32(col_scale)
+    out = np.empty((rows, cols), dtype=np.uint8)
+    plan = np.empty((rows, cols), dtype=np.float64) if return_plan else None
+    te = ctypes.c_double(0.0)
+    stats = np.zeros(4, dtype=np.int64)
+    rc = _load().tsenor_oracle_mask(_ptr(W), rows, cols, cols, _ptr(cs), N, M, float(tau), int(tau_mode), T, L,
+                                    int(strict_paper), int(cols_first), _ptr(out), _ptr(plan),
+                                    ctypes.cast(ctypes.byref(te), ctypes.c_void_p), _ptr(stats))
+    if rc:
+        raise ValueError(f"tsenor_oracle_mask failed: {rc}")
+    res = {"mask": out, "stats": stats, "tau_eff": te.value}
+    if return_plan:
+        res["log_S"] = plan
+    return res
