@@ -1,0 +1,125 @@
+/*
+ * tsenor.h - C ABI of the MI355X (gfx950) transposable N:M mask finder.
+ *
+ * The library computes, for every MxM block of a weight-importance matrix, a 0/1
+ * mask with exactly N ones in every row and every column of the block that keeps
+ * as much importance as possible (paper Sec. 3, Eq. 1 and Eq. 2).  Each block is
+ * relaxed to an entropy-regularised capacitated transport problem (Sec. 3.2,
+ * Eq. 4), solved with T Dykstra iterations (Algorithm 1) and rounded to a mask by
+ * greedy selection plus swap-based local search (Sec. 3.3, Algorithm 2, Eq. 5).
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer named in a problem is a DEVICE pointer owned by the caller;
+ *     the library never frees or keeps them.  The tsenor_problem structs
+ *     themselves live in HOST memory and are read before the call returns.
+ *   - Work is enqueued on `stream` and is NOT synchronised; outputs are valid
+ *     once the stream has reached the end of the enqueued work.
+ *   - Return value: TSENOR_OK (0) or a negative tsenor_status.  Arguments are
+ *     validated on the host before anything is enqueued; on error nothing was
+ *     enqueued.  Inputs must be finite; NaN/Inf weights give unspecified masks.
+ *   - Matrices are row-major; element (i, j) of W is W[i * ld + j]; the mask and
+ *     the optional plan use leading dimension `cols`.
+ *   - rows and cols must be multiples of M (the method never pads, Sec. 3.1);
+ *     M must be one of 4, 8, 16, 32, 64 and 0 <= N <= M.  N == 0 and N == M are
+ *     answered with the all-zero / all-one mask without iterating.
+ *   - The arithmetic of the Dykstra iterations, the sort keys and the swap scores
+ *     is IEEE double precision on the device.
+ */
+#ifndef TSENOR_H
+#define TSENOR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* opaque stream handle: pass a hipStream_t (NULL = the default stream) */
+typedef void* tsenor_stream_t;
+
+typedef enum tsenor_status {
+  TSENOR_OK = 0,
+  TSENOR_ERR_NULL = -1,        /* a required pointer is NULL */
+  TSENOR_ERR_SHAPE = -2,       /* rows/cols <= 0, not multiples of M, ld < cols, or too large */
+  TSENOR_ERR_NM = -3,          /* N < 0 or N > M */
+  TSENOR_ERR_UNSUPPORTED = -4, /* M not in {4, 8, 16, 32, 64}, unknown dtype, tau_mode or flag */
+  TSENOR_ERR_PARAM = -5,       /* tau <= 0 or not finite, iters < 0, tau out of the supported range */
+  TSENOR_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or smaller than tsenor_workspace_bytes */
+  TSENOR_ERR_HIP = -7          /* a HIP call failed; hipGetLastError() holds the cause */
+} tsenor_status;
+
+enum { TSENOR_F32 = 0, TSENOR_BF16 = 1 }; /* storage type of W; bf16 is widened exactly */
+
+/* How `tau` forms the log-kernel K of Algorithm 1 (S^(0) = exp(K)):
+ *   ABSOLUTE        K_ij = tau * imp_ij, Algorithm 1 line 1 as printed.
+ *   REL_MATRIX_MAX  K_ij = imp_ij / (tau * max_ij imp_ij): the entropy weight 1/tau_eff of Eq. 4 is
+ *                   tau times the largest importance of this matrix (the parameter choice of
+ *                   App. B.1, "0.005 max|W|", read so that it is consistent with Eq. 4).
+ * The log-kernel may not exceed 690 (natural-log units); larger values are a TSENOR_ERR_PARAM in
+ * ABSOLUTE mode when detectable on the host (tau itself > 690 / FLT_MIN is not), and in
+ * REL_MATRIX_MAX mode tau must be >= 1/690. */
+enum { TSENOR_TAU_ABSOLUTE = 0, TSENOR_TAU_REL_MATRIX_MAX = 1 };
+
+enum {
+  /* Algorithm 2 exactly as printed: at most `local_search_steps` rounds and a swap is applied only
+   * when its score is > 0; blocks may then be left with fewer than N ones in some rows/columns.
+   * Without this flag local search runs until every row and column holds N ones and applies the
+   * best valid swap even if its score is <= 0.  (A valid swap always exists while a row i and a
+   * column j are short: greedy leaves S_ij = 1 wherever both are short, so every row with a 0 in
+   * column j is full, and its N ones cannot all sit in the fewer than N columns where row i has ones.) */
+  TSENOR_FLAG_STRICT_PAPER = 1u << 0,
+  /* project onto the column-sum set before the row-sum set (the order of the listing in App. A.2);
+   * default is rows first as in Algorithm 1 */
+  TSENOR_FLAG_COLS_FIRST = 1u << 1
+};
+
+typedef struct tsenor_problem {
+  const void* W;          /* device, rows x ld elements of `dtype`; read-only */
+  int32_t dtype;          /* TSENOR_F32 or TSENOR_BF16 */
+  int64_t rows, cols, ld; /* ld in elements, >= cols */
+  const float* col_scale; /* device, optional (NULL = none), length cols: importance = |W_ij| * col_scale[j]
+                             as one float multiply (Sec. 4, Wanda-style importance); values must be >= 0 */
+  int32_t N, M;           /* keep N of every M, in rows and in columns of every MxM block */
+  double tau;             /* > 0, see tau_mode */
+  int32_t tau_mode;       /* TSENOR_TAU_ABSOLUTE or TSENOR_TAU_REL_MATRIX_MAX */
+  int32_t iters;          /* T of Algorithm 1: exactly this many iterations, no early exit; 0 = round the
+                             importance itself */
+  int32_t local_search_steps; /* L of Algorithm 2 (paper: 10); the round limit under STRICT_PAPER, and the
+                                 threshold of stats_out[2] otherwise */
+  uint32_t flags;         /* TSENOR_FLAG_* */
+  uint8_t* mask;          /* device out, rows x cols bytes, 1 = keep */
+  double* plan_out;       /* device out, optional (NULL = skip): rows x cols doubles, S^(T) of Algorithm 1 */
+  double* tau_eff_out;    /* device out, optional: the multiplier tau_eff with K = tau_eff * imp */
+  int64_t* stats_out;     /* device out, optional, 4 counters summed over blocks: [0] ones still missing after
+                             greedy selection, [1] swaps applied with score <= 0, [2] blocks that needed more
+                             than local_search_steps rounds, [3] ones still missing at return (STRICT_PAPER) */
+} tsenor_problem;
+
+/* Bytes of device scratch that tsenor_mask_ex / tsenor_mask_batched need for these problems
+ * (the sum over the batch).  0 on invalid arguments. */
+size_t tsenor_workspace_bytes(const tsenor_problem* problems, int count);
+
+/* The whole path (tile load -> Algorithm 1 -> Algorithm 2 -> mask write) for one matrix.
+ * `workspace`: device memory, 256-byte aligned, at least tsenor_workspace_bytes(p, 1) bytes; its contents
+ * are scratch.  Calls that overlap in time must not share a workspace. */
+int tsenor_mask_ex(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream);
+
+/* The same for `count` matrices (for example the seven projections of a decoder layer), enqueued
+ * back to back on one stream; problems may differ in every field. */
+int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspace, size_t workspace_bytes,
+                        tsenor_stream_t stream);
+
+/* Convenience form of the paper's problem statement: fp32 weights, importance |W|, ld = cols,
+ * K = tau * |W| (ABSOLUTE), default local search.  Allocates its scratch with hipMallocAsync on
+ * `stream` and frees it with hipFreeAsync; everything else as tsenor_mask_ex. */
+int tsenor_mask(const float* W, int64_t rows, int64_t cols, int N, int M, float tau, int iters, uint8_t* mask,
+                tsenor_stream_t stream);
+
+const char* tsenor_status_string(int status);
+int tsenor_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSENOR_H */

@@ -1,0 +1,34 @@
+"""Build step of the HIP library: one hipcc invocation for gfx950, output in-tree next to the binding."""
+from __future__ import annotations
+
+import os
+import subprocess
+from pathlib import Path
+
+PKG = Path(__file__).resolve().parent
+ROOT = PKG.parent
+SOURCES = [PKG / "csrc" / "tsenor.hip"]
+OUTPUT = PKG / "libtsenor.so"
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    # packed fp32 instructions are kept out of every kernel
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    f"-I{ROOT / 'include'}",
+]
+
+
+def build(verbose: bool = False) -> Path:
+    """Compile every HIP source into libtsenor.so (always recompiles)."""
+    tmp = OUTPUT.with_suffix(f".so.tmp{os.getpid()}")
+    cmd = [HIPCC, *FLAGS, "-o", str(tmp), *map(str, SOURCES)]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, OUTPUT)
+    return OUTPUT
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))
