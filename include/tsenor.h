@@ -116,6 +116,16 @@ int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspa
 int tsenor_mask(const float* W, int64_t rows, int64_t cols, int N, int M, float tau, int iters, uint8_t* mask,
                 tsenor_stream_t stream);
 
+/* Measurement aid for benchmarks: runs tsenor_mask_ex `repeats` times (1..4096) back to back on `stream`
+ * with HIP events recorded at the stage boundaries, SYNCHRONISES the stream, and writes to the HOST array
+ * stage_ms[TSENOR_NUM_STAGES] the mean duration in milliseconds of
+ *   [0] workspace reset + matrix maximum (REL_MATRIX_MAX only)   [1] tile load + Algorithm 1 + sort
+ *   [2] greedy selection (Algorithm 2 lines 1-6)                 [3] local search + mask write.
+ * Outputs are those of the last repeat.  Creates and destroys its events; allocates no device memory. */
+#define TSENOR_NUM_STAGES 4
+int tsenor_mask_ex_profile(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream,
+                           int repeats, float* stage_ms);
+
 const char* tsenor_status_string(int status);
 int tsenor_version(void);
 

@@ -30,7 +30,7 @@ TSENOR_FLAG_STRICT_PAPER = 1 << 0
 TSENOR_FLAG_COLS_FIRST = 1 << 1
 
 EXPORTS = (
-    "tsenor_workspace_bytes", "tsenor_mask_ex", "tsenor_mask_batched", "tsenor_mask",
+    "tsenor_workspace_bytes", "tsenor_mask_ex", "tsenor_mask_batched", "tsenor_mask", "tsenor_mask_ex_profile",
     "tsenor_status_string", "tsenor_version",
 )
 
@@ -83,6 +83,9 @@ def load() -> ctypes.CDLL:
         lib.tsenor_mask.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                     ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         lib.tsenor_mask.restype = ctypes.c_int
+        lib.tsenor_mask_ex_profile.argtypes = [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int,
+                                               ctypes.POINTER(ctypes.c_float)]
+        lib.tsenor_mask_ex_profile.restype = ctypes.c_int
         lib.tsenor_status_string.argtypes = [ctypes.c_int]
         lib.tsenor_status_string.restype = ctypes.c_char_p
         lib.tsenor_version.restype = ctypes.c_int
@@ -157,6 +160,21 @@ def tsenor_mask_ex(problem, workspace, stream=None) -> None:
                                workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != TSENOR_OK:
         raise TsenorError(rc, "tsenor_mask_ex")
+
+
+NUM_STAGES = 4
+STAGE_NAMES = ("reset+absmax", "dykstra+sort", "greedy", "local_search+write")
+
+
+def tsenor_mask_ex_profile(problem, workspace, repeats, stream=None):
+    """Run the path ``repeats`` times, synchronise, return the mean per-stage durations in ms."""
+    ms = (ctypes.c_float * NUM_STAGES)()
+    rc = load().tsenor_mask_ex_profile(ctypes.byref(problem), ctypes.c_void_p(workspace.data_ptr()),
+                                       workspace.numel() * workspace.element_size(), _stream_handle(stream),
+                                       int(repeats), ms)
+    if rc != TSENOR_OK:
+        raise TsenorError(rc, "tsenor_mask_ex_profile")
+    return [float(x) for x in ms]
 
 
 def tsenor_mask(W, N, M, tau, iters, mask=None, stream=None):

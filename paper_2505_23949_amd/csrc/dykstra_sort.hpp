@@ -1,0 +1,347 @@
+// Tile load, Algorithm 1 (Dykstra iterations) and the sort that feeds Algorithm 2, one kernel.
+//
+// How Algorithm 1 is evaluated.  With A = log S + log Q, the cap step (lines 5-6) gives
+// log S = min(A, 0) and log Q = max(A, 0) after every iteration, and one iteration adds a row term
+// and a column term to A.  So A = K + f_i + g_j with K = tau_eff * importance: the whole Dykstra
+// state of a block is K plus 2M potentials.  The kernel keeps kappa = exp(K - max K) and the scalings
+// U_i = exp(f_i), V_j = exp(g_j) in double precision and iterates
+//     e_ij = min(kappa_ij V_j U_i, 1);   R_i = N / sum_j e_ij;   C_j = N / sum_i e_ij R_i;
+//     U_i *= R_i;   V_j *= C_j
+// which is lines 3-6 of Algorithm 1 in exact arithmetic: the row scaling acts on the plan capped by
+// the previous iteration, the column scaling on the row-scaled plan, and the cap with its dual is the
+// min(., 1) at the top of the next pass (App. A.2 listing, same order of operations).  Four
+// double-precision operations per entry and iteration and no transcendental in the loop.
+//
+// Layout.  A block is spread over LPB = GX*GY lanes as a GY x GX grid of TH x TW register tiles
+// (TH = M/GY rows, TW = M/GX columns); a wave holds 64/LPB blocks.  Row sums are reduced across the GX
+// lanes of a lane-row by recursive halving (reduce-scatter): after log2(GX) exchange steps every lane
+// owns TH/GX complete row sums, computes their reciprocals once, and the results are gathered back the
+// same way.  To keep every exchange a fixed set of registers (no selects), register a of lane gx holds
+// tile row a ^ (gx << log2(TH/GX)); columns likewise over the GY lanes of a lane-column.
+#pragma once
+#include "lanes.hpp"
+#include "problem.hpp"
+
+namespace tsenor_dev {
+
+constexpr double kMinLogKernel = -700.0;  // exp(-700) is still a normal double
+constexpr int kIdxBits = 12;              // flat index within a block: up to 64*64 entries
+
+constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
+
+// Per-M tiling.  XM[s] / YM[s]: lane masks of the exchange steps along a lane-row / lane-column.
+// The top bit of XM[s] is lane bit NX-1-s (mirror masks keep the exchanges on DPP); YM[s] is a single
+// lane bit, listed cheapest mechanism first because the first step moves the most registers.
+template <int M>
+struct Tiling;
+template <>
+struct Tiling<4> {
+  static constexpr int NX = 0, NY = 0;
+  static constexpr int XM[1] = {1}, YM[1] = {1};
+  static constexpr bool STORE_E = true;
+};
+template <>
+struct Tiling<8> {
+  static constexpr int NX = 1, NY = 1;
+  static constexpr int XM[1] = {1}, YM[1] = {2};
+  static constexpr bool STORE_E = true;
+};
+template <>
+struct Tiling<16> {
+  static constexpr int NX = 2, NY = 1;  // 8 lanes per block, 8 x 4 tiles
+  static constexpr int XM[2] = {3, 1}, YM[1] = {4};
+  static constexpr bool STORE_E = true;
+};
+template <>
+struct Tiling<32> {
+  static constexpr int NX = 3, NY = 2;  // 32 lanes per block, 8 x 4 tiles
+  static constexpr int XM[3] = {7, 3, 1}, YM[2] = {8, 16};
+  static constexpr bool STORE_E = true;
+};
+template <>
+struct Tiling<64> {
+  static constexpr int NX = 3, NY = 3;  // 64 lanes per block, 8 x 8 tiles; too large to hold e as well
+  static constexpr int XM[3] = {7, 3, 1}, YM[3] = {8, 16, 32};
+  static constexpr bool STORE_E = false;
+};
+
+// 1/d to double precision: hardware estimate plus two Newton steps.
+__device__ __forceinline__ double fast_rcp(double d) {
+  double x = __builtin_amdgcn_rcp(d);
+  x = fma(fma(-d, x, 1.0), x, x);
+  x = fma(fma(-d, x, 1.0), x, x);
+  return x;
+}
+
+// Recursive halving over the lanes of a lane-row.  v[0..TH): partial sums, register a <-> tile row
+// a ^ (gx << SH).  Afterwards v[0 .. TH >> NX) hold complete sums.
+template <class T, int TH, int S = 0>
+__device__ __forceinline__ void reduce_scatter_x(double (&v)[TH]) {
+  if constexpr (S < T::NX) {
+    constexpr int SH = ilog2(TH) - T::NX;
+    constexpr int h = TH >> (S + 1);
+    constexpr int am = (T::XM[S] << SH) & (2 * h - 1);  // register index of the partner's matching value
+#pragma unroll
+    for (int a = 0; a < h; ++a) v[a] += lane_xor<T::XM[S]>(v[a ^ am]);
+    reduce_scatter_x<T, TH, S + 1>(v);
+  }
+}
+template <class T, int TH, int S = T::NX - 1>
+__device__ __forceinline__ void all_gather_x(double (&v)[TH]) {
+  if constexpr (S >= 0) {
+    constexpr int SH = ilog2(TH) - T::NX;
+    constexpr int h = TH >> (S + 1);
+    constexpr int am = (T::XM[S] << SH) & (2 * h - 1);
+#pragma unroll
+    for (int a = 0; a < h; ++a) v[a ^ am] = lane_xor<T::XM[S]>(v[a]);
+    all_gather_x<T, TH, S - 1>(v);
+  }
+}
+// The same over the lanes of a lane-column; step s pairs lanes that differ in lane bit YM[s].
+template <class T, int TW, int S = 0>
+__device__ __forceinline__ void reduce_scatter_y(double (&v)[TW]) {
+  if constexpr (S < T::NY) {
+    constexpr int h = TW >> (S + 1);
+#pragma unroll
+    for (int b = 0; b < h; ++b) v[b] += lane_xor<T::YM[S]>(v[b + h]);
+    reduce_scatter_y<T, TW, S + 1>(v);
+  }
+}
+template <class T, int TW, int S = T::NY - 1>
+__device__ __forceinline__ void all_gather_y(double (&v)[TW]) {
+  if constexpr (S >= 0) {
+    constexpr int h = TW >> (S + 1);
+#pragma unroll
+    for (int b = 0; b < h; ++b) v[b + h] = lane_xor<T::YM[S]>(v[b]);
+    all_gather_y<T, TW, S - 1>(v);
+  }
+}
+// register offset of a lane along y: lane bit YM[s] set <-> register bit log2(TW >> (s+1))
+template <class T, int TW, int S = 0>
+__device__ __forceinline__ int reg_xor_y(int q) {
+  if constexpr (S < T::NY)
+    return ((q & T::YM[S]) ? (TW >> (S + 1)) : 0) | reg_xor_y<T, TW, S + 1>(q);
+  else
+    return 0;
+}
+
+__device__ __forceinline__ void compare_exchange(double& lo, double& hi) {
+  const double a = fmin(lo, hi), b = fmax(lo, hi);
+  lo = a;
+  hi = b;
+}
+
+// Ascending bitonic sort of E*LPB distinct positive doubles spread over LPB lanes (position q*E + r).
+// Every merge starts with the mirrored compare (position p against p ^ (k-1)), after which the smaller
+// key always belongs at the lower position, so no direction flags are needed.
+
+template <int E, int LPB, int J>
+__device__ __forceinline__ void sort_half_cleaners(double (&c)[E], int q) {
+  if constexpr (J >= 1) {
+    if constexpr (J < E) {
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        const int pr = r ^ J;
+        if (pr > r) compare_exchange(c[r], c[pr]);
+      }
+    } else {
+      constexpr int lm = J / E;
+      const bool keep_min = (q & lm) == 0;
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        const double o = lane_xor<lm>(c[r]);
+        c[r] = ((c[r] < o) == keep_min) ? c[r] : o;
+      }
+    }
+    sort_half_cleaners<E, LPB, J / 2>(c, q);
+  }
+}
+
+template <int E, int LPB, int K = 2>
+__device__ __forceinline__ void sort_ascending(double (&c)[E], int q) {
+  if constexpr (K <= E * LPB) {
+    if constexpr (K <= E) {
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        const int pr = r ^ (K - 1);
+        if (pr > r) compare_exchange(c[r], c[pr]);
+      }
+    } else {
+      constexpr int lm = K / E - 1;
+      const bool keep_min = (q & (K / E / 2)) == 0;
+      double o[E];
+#pragma unroll
+      for (int r = 0; r < E; ++r) o[r] = lane_xor<lm>(c[E - 1 - r]);
+#pragma unroll
+      for (int r = 0; r < E; ++r) c[r] = ((c[r] < o[r]) == keep_min) ? c[r] : o[r];
+    }
+    sort_half_cleaners<E, LPB, K / 4>(c, q);
+    sort_ascending<E, LPB, K * 2>(c, q);
+  }
+}
+
+template <int M>
+__global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, const WsHeader* hdr, unsigned short* order,
+                                                            double* plan_out, double* tau_eff_out) {
+  using T = Tiling<M>;
+  constexpr int GX = 1 << T::NX, GY = 1 << T::NY, TH = M / GY, TW = M / GX, LPB = GX * GY, BPW = kWave / LPB,
+                E = TH * TW, OWN_R = TH / GX, OWN_C = TW / GY, SHX = ilog2(TH) - T::NX;
+  static_assert(TH >= GX && TW >= GY, "every lane must end a reduce-scatter with at least one sum");
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+  const int q = lane % LPB, gx = q % GX, gy = q / GX;
+  int64_t blk = wave * BPW + lane / LPB;
+  const bool active = blk < p.nblocks;
+  if (!active) blk = p.nblocks - 1;  // idle lanes shadow the last block and write nothing
+  const int64_t r0 = (blk / p.bc) * M, c0 = (blk % p.bc) * M;
+  const double tau_eff = tau_eff_of(p, hdr);
+  if (tau_eff_out && blockIdx.x == 0 && threadIdx.x == 0) *tau_eff_out = tau_eff;
+
+  // register (a, b) of this lane <-> in-kernel coordinates (ri, cj) of the block
+  const int rx = gx << SHX, ry = reg_xor_y<T, TW>(q);
+  auto ri_of = [&](int a) { return gy * TH + (a ^ rx); };
+  auto cj_of = [&](int b) { return gx * TW + (b ^ ry); };
+  // with `transpose` the in-kernel rows are the matrix columns, which turns "rows first" into
+  // "columns first" (TSENOR_FLAG_COLS_FIRST)
+  auto mat_row = [&](int ri, int cj) { return p.transpose ? cj : ri; };
+  auto mat_col = [&](int ri, int cj) { return p.transpose ? ri : cj; };
+
+  double kap[TH][TW];
+  double mx = 0.0;
+#pragma unroll
+  for (int a = 0; a < TH; ++a)
+#pragma unroll
+    for (int b = 0; b < TW; ++b) {
+      const int ri = ri_of(a), cj = cj_of(b);
+      const float imp = load_importance(p, r0 + mat_row(ri, cj), c0 + mat_col(ri, cj));
+      kap[a][b] = tau_eff * (double)imp;  // K of Algorithm 1 line 1
+      mx = fmax(mx, kap[a][b]);
+    }
+  mx = group_max<LPB>(mx);
+
+  double c[E];  // sort keys
+  if (p.T == 0) {
+    // no iterations: the greedy order is descending K itself
+#pragma unroll
+    for (int a = 0; a < TH; ++a)
+#pragma unroll
+      for (int b = 0; b < TW; ++b) {
+        const int ri = ri_of(a), cj = cj_of(b);
+        const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(kap[a][b]);
+        const unsigned long long key = (0x40A0000000000000ull - bits) & ~((1ull << kIdxBits) - 1);
+        c[a * TW + b] = __longlong_as_double((long long)(key | idx));
+        if (plan_out && active)
+          plan_out[(r0 + mat_row(ri, cj)) * p.cols + c0 + mat_col(ri, cj)] = exp(kap[a][b]);
+      }
+  } else {
+#pragma unroll
+    for (int a = 0; a < TH; ++a)
+#pragma unroll
+      for (int b = 0; b < TW; ++b) {
+        kap[a][b] = exp(fmax(kap[a][b] - mx, kMinLogKernel));
+        __builtin_amdgcn_sched_barrier(0);  // one exp at a time: interleaving them only costs registers
+      }
+
+    const double Nd = (double)p.N;
+    double U[TH], V[TW];
+#pragma unroll
+    for (int a = 0; a < TH; ++a) U[a] = 1.0;
+#pragma unroll
+    for (int b = 0; b < TW; ++b) V[b] = 1.0;
+
+#ifdef TS_UNROLL1
+#pragma unroll 1
+#endif
+    for (int t = 0; t < p.T; ++t) {
+      double e[T::STORE_E ? TH : 1][T::STORE_E ? TW : 1];
+      double R[TH], C[TW];
+      // projection onto C1 (Algorithm 1 line 3) of the plan capped by the previous iteration
+#pragma unroll
+      for (int a = 0; a < TH; ++a) {
+        double s = 0.0;
+#pragma unroll
+        for (int b = 0; b < TW; ++b) {
+          const double ev = fmin(fmax((kap[a][b] * V[b]) * U[a], 0.0), 1.0);
+          if constexpr (T::STORE_E) e[a][b] = ev;
+          s += ev;
+        }
+        R[a] = s;
+      }
+      reduce_scatter_x<T, TH>(R);
+#pragma unroll
+      for (int a = 0; a < OWN_R; ++a) R[a] = Nd * fast_rcp(fmax(R[a], 1e-300));
+      all_gather_x<T, TH>(R);
+      // projection onto C2 (line 4)
+#pragma unroll
+      for (int b = 0; b < TW; ++b) {
+        double s = 0.0;
+#pragma unroll
+        for (int a = 0; a < TH; ++a) {
+          double ev;
+          if constexpr (T::STORE_E)
+            ev = e[a][b];
+          else
+            ev = fmin(fmax((kap[a][b] * V[b]) * U[a], 0.0), 1.0);
+          s = fma(ev, R[a], s);
+        }
+        C[b] = s;
+      }
+      reduce_scatter_y<T, TW>(C);
+#pragma unroll
+      for (int b = 0; b < OWN_C; ++b) C[b] = Nd * fast_rcp(fmax(C[b], 1e-300));
+      all_gather_y<T, TW>(C);
+#pragma unroll
+      for (int a = 0; a < TH; ++a) U[a] *= R[a];
+#pragma unroll
+      for (int b = 0; b < TW; ++b) V[b] *= C[b];
+      // lines 5-6 (cap and dual update) are the min(., 1) at the top of the next pass
+    }
+
+    // fresh copies of the lane offsets: addresses are recomputed here rather than kept alive in
+    // registers across the iteration loop
+    int rx2 = rx, ry2 = ry;
+    asm volatile("" : "+v"(rx2), "+v"(ry2));
+    double lu[TH], lv[TW];
+#pragma unroll
+    for (int a = 0; a < TH; ++a) {
+      lu[a] = log(U[a]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int b = 0; b < TW; ++b) {
+      lv[b] = log(V[b]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int a = 0; a < TH; ++a)
+#pragma unroll
+      for (int b = 0; b < TW; ++b) {
+        const int ri = gy * TH + (a ^ rx2), cj = gx * TW + (b ^ ry2);
+        const int64_t mr = r0 + mat_row(ri, cj), mc = c0 + mat_col(ri, cj);
+        const double K = tau_eff * (double)load_importance(p, mr, mc);
+        // log S^(T) = min(K + f_i + g_j, 0)
+        const double key = fmin(fmax(K - mx, kMinLogKernel) + (lu[a] + lv[b]), 0.0);
+        if (plan_out && active) plan_out[mr * p.cols + mc] = exp(key);
+        const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(fabs(key));
+        // descending key, ties by ascending flat index; + 2^52 keeps the pattern a normal double
+        c[a * TW + b] =
+            __longlong_as_double((long long)(((bits & ~((1ull << kIdxBits) - 1)) | idx) + (1ull << 52)));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+  }
+
+#ifndef TS_NO_SORT
+  sort_ascending<E, LPB>(c, q);
+#endif
+
+  if (active) {
+    unsigned short* dst = order + blk * (int64_t)(M * M) + q * E;
+#pragma unroll
+    for (int r = 0; r < E; ++r)
+      dst[r] = (unsigned short)((unsigned long long)__double_as_longlong(c[r]) & ((1ull << kIdxBits) - 1));
+  }
+}
+
+}  // namespace tsenor_dev
