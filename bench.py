@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--cols", type=int, default=0, help="override cols (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one elementwise pass over 256 MiB (reads 256 MiB, writes 256 MiB): the "
+                         "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (blocks are independent; see DESIGN.md for how the "
@@ -68,6 +71,13 @@ def main() -> int:
     prob = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask, col_scale=cs, tau_mode=w.tau_mode,
                                 stats_out=stats)
     work = torch.empty(binding.tsenor_workspace_bytes([prob]), dtype=torch.uint8, device=dev)
+
+    if args.calibrate_copy:
+        ref_in = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        ref_out = torch.empty_like(ref_in)
+        torch.add(ref_in, 1.0, out=ref_out)
+        torch.cuda.synchronize()
+        del ref_in, ref_out
 
     for _ in range(args.warmup):
         binding.tsenor_mask_ex(prob, work)
