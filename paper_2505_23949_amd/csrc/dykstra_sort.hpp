@@ -197,10 +197,14 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
   const double tau_eff = tau_eff_of(p, hdr);
   if (tau_eff_out && blockIdx.x == 0 && threadIdx.x == 0) *tau_eff_out = tau_eff;
 
-  // register (a, b) of this lane <-> in-kernel coordinates (ri, cj) of the block
+  // register (a, b) of this lane <-> in-kernel coordinates (ri, cj) of the block.  Each phase of the
+  // kernel takes its own opaque copy of the lane offsets, so that element addresses are recomputed where
+  // they are needed instead of being kept in registers across the iteration loop.
   const int rx = gx << SHX, ry = reg_xor_y<T, TW>(q);
-  auto ri_of = [&](int a) { return gy * TH + (a ^ rx); };
-  auto cj_of = [&](int b) { return gx * TW + (b ^ ry); };
+  auto fresh = [](int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+  };
   // with `transpose` the in-kernel rows are the matrix columns, which turns "rows first" into
   // "columns first" (TSENOR_FLAG_COLS_FIRST)
   auto mat_row = [&](int ri, int cj) { return p.transpose ? cj : ri; };
@@ -212,7 +216,7 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
   for (int a = 0; a < TH; ++a)
 #pragma unroll
     for (int b = 0; b < TW; ++b) {
-      const int ri = ri_of(a), cj = cj_of(b);
+      const int ri = gy * TH + (a ^ rx), cj = gx * TW + (b ^ ry);
       const float imp = load_importance(p, r0 + mat_row(ri, cj), c0 + mat_col(ri, cj));
       kap[a][b] = tau_eff * (double)imp;  // K of Algorithm 1 line 1
       mx = fmax(mx, kap[a][b]);
@@ -222,11 +226,12 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
   double c[E];  // sort keys
   if (p.T == 0) {
     // no iterations: the greedy order is descending K itself
+    const int rx0 = fresh(rx), ry0 = fresh(ry);
 #pragma unroll
     for (int a = 0; a < TH; ++a)
 #pragma unroll
       for (int b = 0; b < TW; ++b) {
-        const int ri = ri_of(a), cj = cj_of(b);
+        const int ri = gy * TH + (a ^ rx0), cj = gx * TW + (b ^ ry0);
         const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
         const unsigned long long bits = (unsigned long long)__double_as_longlong(kap[a][b]);
         const unsigned long long key = (0x40A0000000000000ull - bits) & ~((1ull << kIdxBits) - 1);
@@ -250,9 +255,6 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
 #pragma unroll
     for (int b = 0; b < TW; ++b) V[b] = 1.0;
 
-#ifdef TS_UNROLL1
-#pragma unroll 1
-#endif
     for (int t = 0; t < p.T; ++t) {
       double e[T::STORE_E ? TH : 1][T::STORE_E ? TW : 1];
       double R[TH], C[TW];
@@ -300,8 +302,7 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
 
     // fresh copies of the lane offsets: addresses are recomputed here rather than kept alive in
     // registers across the iteration loop
-    int rx2 = rx, ry2 = ry;
-    asm volatile("" : "+v"(rx2), "+v"(ry2));
+    const int rx2 = fresh(rx), ry2 = fresh(ry);
     double lu[TH], lv[TW];
 #pragma unroll
     for (int a = 0; a < TH; ++a) {
@@ -332,9 +333,7 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
       }
   }
 
-#ifndef TS_NO_SORT
   sort_ascending<E, LPB>(c, q);
-#endif
 
   if (active) {
     unsigned short* dst = order + blk * (int64_t)(M * M) + q * E;

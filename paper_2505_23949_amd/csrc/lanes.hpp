@@ -53,6 +53,32 @@ __device__ __forceinline__ double lane_xor(double v) {
   }
 }
 
+// 32-bit variant of lane_xor
+template <int MASK>
+__device__ __forceinline__ int lane_xor_i32(int v) {
+  static_assert(MASK > 0 && MASK < kWave, "lane mask");
+  if constexpr (MASK == 1) {
+    return __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);
+  } else if constexpr (MASK == 2) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);
+  } else if constexpr (MASK == 3) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x1B, 0xF, 0xF, true);
+  } else if constexpr (MASK == 7) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);
+  } else if constexpr (MASK == 15) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);
+  } else if constexpr (MASK == 8) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x128, 0xF, 0xF, true);
+  } else if constexpr (MASK < 32) {
+    return __builtin_amdgcn_ds_swizzle(v, (MASK << 10) | 0x1F);
+  } else if constexpr (MASK == 32) {
+    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+    return (int)((__lane_id() & 32) ? r[0] : r[1]);
+  } else {
+    return lane_xor_i32<32>(lane_xor_i32<(MASK & 31)>(v));
+  }
+}
+
 // max over the lanes of a group of LPB consecutive lanes (LPB a power of two)
 template <int LPB, int STEP = 1>
 __device__ __forceinline__ double group_max(double v) {

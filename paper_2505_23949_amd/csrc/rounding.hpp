@@ -1,6 +1,7 @@
 // Algorithm 2: greedy selection (one lane per block) and local search plus the mask write.
 #pragma once
 #include <limits>
+#include <type_traits>
 
 #include "lanes.hpp"
 #include "problem.hpp"
@@ -48,108 +49,141 @@ __global__ __launch_bounds__(kWave) void greedy_kernel(const unsigned short* ord
   if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
 }
 
-// Algorithm 2 lines 7-13 and the mask write.  L3 lanes per block (M <= L3 <= 64), 64/L3 blocks per wave.
-template <int M, int L3>
+// Best candidate of Eq. (5) held by a lane: score, flat index i'*M+j' (MM = none).  Higher score wins,
+// equal scores go to the lower flat index.
+struct SwapBest {
+  double score;
+  int arg;
+};
+template <int MM>
+__device__ __forceinline__ SwapBest better_of(SwapBest a, SwapBest b) {
+  const bool take_b = b.arg != MM && (a.arg == MM || b.score > a.score || (b.score == a.score && b.arg < a.arg));
+  return take_b ? b : a;
+}
+template <int M, int STEP = 1>
+__device__ __forceinline__ SwapBest group_best(SwapBest v) {
+  if constexpr (STEP < M) {
+    SwapBest o;
+    o.score = lane_xor<STEP>(v.score);
+    o.arg = lane_xor_i32<STEP>(v.arg);
+    return group_best<M, STEP * 2>(better_of<M * M>(v, o));
+  } else {
+    return v;
+  }
+}
+
+// Algorithm 2 lines 7-13 and the mask write.  M lanes per block (lane r owns row r and column r of the
+// block as bit masks), 64/M blocks per wave, one wave per workgroup.
+template <int M>
 __global__ __launch_bounds__(kWave) void finalize_kernel(DevProblem p, const unsigned short* order,
                                                          const unsigned int* accept, uint8_t* mask, WsHeader* hdr,
-                                                         int64_t* stats_out) {
-  constexpr int MM = M * M, G = kWave / L3, WORDS = MM >= 32 ? MM / 32 : 1, PER_WORD = MM >= 32 ? 32 : MM;
-  static_assert(L3 >= M && kWave % L3 == 0 && MM % L3 == 0, "lanes per block");
+                                                         int wide_store) {
+  using mask_t = typename std::conditional<(M > 32), unsigned long long, unsigned int>::type;
+  constexpr int MM = M * M, G = kWave / M, WORDS = MM >= 32 ? MM / 32 : 1, PER_WORD = MM >= 32 ? 32 : MM;
   __shared__ float imp[G][MM];
-  __shared__ unsigned char S[G][MM];
-  __shared__ int Rc[G][M], Cc[G][M];
-  const int lane = threadIdx.x, g = lane / L3, ql = lane % L3;
+  __shared__ mask_t rowm[G][M], colm[G][M];  // rowm[r] bit c == colm[c] bit r == S[r][c]
+  const int lane = threadIdx.x, g = lane / M, ql = lane % M;
   int64_t blk = (int64_t)blockIdx.x * G + g;
   const bool active = blk < p.nblocks;
-  if (!active) blk = p.nblocks - 1;
+  if (!active) blk = p.nblocks - 1;  // idle groups shadow the last block and write nothing
   const int64_t r0 = (blk / p.bc) * M, c0 = (blk % p.bc) * M;
+  const mask_t one = 1;
 
-  for (int e = ql; e < MM; e += L3) {
-    imp[g][e] = load_importance(p, r0 + e / M, c0 + e % M);
-    S[g][e] = 0;
-  }
+  rowm[g][ql] = 0;
+  colm[g][ql] = 0;
   __syncthreads();
-  for (int pos = ql; pos < MM; pos += L3) {
+  // the mask greedy selection left: entry t of the order was kept iff bit t is set
+  for (int k = 0; k < M; ++k) {
+    const int pos = k * M + ql;
     const unsigned int bit = (accept[blk * WORDS + pos / PER_WORD] >> (pos % PER_WORD)) & 1u;
-    if (bit) S[g][order[blk * MM + pos] & (MM - 1)] = 1;
+    if (bit) {
+      const int idx = order[blk * MM + pos] & (MM - 1);
+      atomicOr(&rowm[g][idx / M], one << (idx % M));
+      atomicOr(&colm[g][idx % M], one << (idx / M));
+    }
   }
   __syncthreads();
-  if (ql < M) {
-    int r = 0, c = 0;
-    for (int k = 0; k < M; ++k) {
-      r += S[g][ql * M + k];
-      c += S[g][k * M + ql];
-    }
-    Rc[g][ql] = r;
-    Cc[g][ql] = c;
+  const auto popc = [](mask_t v) { return sizeof(mask_t) == 8 ? __popcll((unsigned long long)v) : __popc((unsigned int)v); };
+  const unsigned long long gmask = (M == 64 ? ~0ull : ((1ull << M) - 1)) << (g * M);
+  const bool any_short = __any(popc(rowm[g][ql]) < p.N);
+  if (any_short) {
+    // local search scores on the importance (Eq. 5), staged in LDS: row k of every block per step
+    for (int k = 0; k < M; ++k) imp[g][k * M + ql] = load_importance(p, r0 + k, c0 + ql);
   }
   __syncthreads();
 
-  const unsigned long long gmask = (L3 == 64 ? ~0ull : ((1ull << L3) - 1)) << (g * L3);
   int rounds = 0, nonpos = 0;
-  bool open = true;  // this block may still take swaps
-  for (;;) {
-    const bool rdef = ql < M && Rc[g][ql < M ? ql : 0] < p.N;
-    const bool cdef = ql < M && Cc[g][ql < M ? ql : 0] < p.N;
-    const unsigned long long rb = __ballot(rdef) & gmask, cb = __ballot(cdef) & gmask;
+  bool open = any_short;  // this block may still take swaps
+  while (any_short) {
+    const mask_t Srow = rowm[g][ql];
+    const unsigned long long rb = __ballot(popc(Srow) < p.N) & gmask;
+    const unsigned long long cb = __ballot(popc(colm[g][ql]) < p.N) & gmask;
     if (rb == 0 || cb == 0 || (p.strict && rounds >= p.L)) open = false;
     if (!__any(open)) break;
-    // Pick i, j: the lowest-index row and column that are short (line 10)
-    const int i = open ? (__ffsll((long long)rb) - 1 - g * L3) : 0;
-    const int j = open ? (__ffsll((long long)cb) - 1 - g * L3) : 0;
-    // line 11: arg max of Eq. (5) over valid (i', j'); ties to the lowest flat index
-    double best = -std::numeric_limits<double>::infinity();
-    int arg = MM;
-    if (open) {
-      for (int e = ql; e < MM; e += L3) {
-        const int ip = e / M, jp = e % M;
-        if (S[g][e] && !S[g][i * M + jp] && !S[g][ip * M + j]) {
-          const double sc = (double)imp[g][i * M + jp] + (double)imp[g][ip * M + j] - (double)imp[g][e];
-          if (arg == MM || sc > best) {
-            best = sc;
-            arg = e;
-          }
+    // line 10: the lowest-index row i and column j that are short
+    const int i = open ? (__ffsll((long long)rb) - 1 - g * M) : 0;
+    const int j = open ? (__ffsll((long long)cb) - 1 - g * M) : 0;
+    // line 11 for i' = this lane: columns j' with S[i'][j'] = 1 and S[i][j'] = 0, provided S[i'][j] = 0
+    mask_t cand = Srow & ~rowm[g][i];
+    if (!open || ((colm[g][j] >> ql) & 1)) cand = 0;
+    const double base = (double)imp[g][ql * M + j];
+    SwapBest best = {-std::numeric_limits<double>::infinity(), MM};
+    while (__any(cand != 0)) {
+      if (cand != 0) {
+        const int jp = sizeof(mask_t) == 8 ? __ffsll((long long)cand) - 1 : __ffs((int)cand) - 1;
+        cand &= cand - 1;
+        const double sc = ((double)imp[g][i * M + jp] + base) - (double)imp[g][ql * M + jp];
+        if (best.arg == MM || sc > best.score) {
+          best.score = sc;
+          best.arg = ql * M + jp;
         }
       }
     }
-#pragma unroll
-    for (int m = 1; m < L3; m <<= 1) {
-      const double ob = __shfl_xor(best, m, kWave);
-      const int oa = __shfl_xor(arg, m, kWave);
-      if (oa != MM && (arg == MM || ob > best || (ob == best && oa < arg))) {
-        best = ob;
-        arg = oa;
-      }
-    }
+    best = group_best<M>(best);
     if (open) ++rounds;
-    bool apply = open && arg != MM;
-    if (p.strict && !(best > 0.0)) apply = false;
+    bool apply = open && best.arg != MM;
+    if (p.strict && !(best.score > 0.0)) apply = false;
     if (open && !apply) open = false;  // nothing changes any more for this block
     __syncthreads();
     if (apply && ql == 0) {
       // line 13: remove (i', j'), insert (i', j) and (i, j')
-      const int ip = arg / M, jp = arg % M;
-      S[g][arg] = 0;
-      S[g][ip * M + j] = 1;
-      S[g][i * M + jp] = 1;
-      Rc[g][i] += 1;
-      Cc[g][j] += 1;
-      if (!(best > 0.0)) ++nonpos;
+      const int ip = best.arg / M, jp = best.arg % M;
+      rowm[g][ip] = (rowm[g][ip] & ~(one << jp)) | (one << j);
+      rowm[g][i] |= one << jp;
+      colm[g][jp] = (colm[g][jp] & ~(one << ip)) | (one << i);
+      colm[g][j] |= one << ip;
+      if (!(best.score > 0.0)) ++nonpos;
     }
     __syncthreads();
   }
 
   if (active) {
-    for (int e = ql; e < MM; e += L3) mask[(r0 + e / M) * p.cols + c0 + e % M] = S[g][e];
+    const mask_t bits = rowm[g][ql];
+    uint8_t* dst = mask + (r0 + ql) * p.cols + c0;
+    if (wide_store) {
+      // 4 mask bytes per 32-bit word: bit k of a nibble goes to byte k
+      unsigned int w[M / 4];
+#pragma unroll
+      for (int k = 0; k < M / 4; ++k) w[k] = (((unsigned int)(bits >> (4 * k)) & 0xFu) * 0x00204081u) & 0x01010101u;
+      if constexpr (M == 4) {
+        *reinterpret_cast<unsigned int*>(dst) = w[0];
+      } else if constexpr (M == 8) {
+        *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < M / 16; ++k)
+          reinterpret_cast<uint4*>(dst)[k] = make_uint4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
+      }
+    } else {
+      for (int k = 0; k < M; ++k) dst[k] = (uint8_t)((bits >> k) & 1);
+    }
+    const int left = p.N - popc(bits);
+    if (left) atomicAdd(&hdr->stats[3], (unsigned long long)left);
     if (ql == 0) {
-      int left = 0;
-      for (int k = 0; k < M; ++k) left += p.N - Rc[g][k];
       if (nonpos) atomicAdd(&hdr->stats[1], (unsigned long long)nonpos);
       if (!p.strict && rounds > p.L) atomicAdd(&hdr->stats[2], 1ull);
-      if (left) atomicAdd(&hdr->stats[3], (unsigned long long)left);
     }
   }
-  (void)stats_out;
 }
 
 }  // namespace tsenor_dev

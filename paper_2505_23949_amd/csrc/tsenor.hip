@@ -30,15 +30,55 @@ __global__ void init_kernel(WsHeader* hdr) {
 }
 
 // Largest importance of the matrix (App. B.1 parameter choice, relative tau).
+// Largest importance of the matrix.  VEC: every thread reads 8 consecutive weights of a row with 16-byte
+// loads (needs cols % 8 == 0 and 16-byte aligned rows and column scale); otherwise one weight at a time.
+template <bool VEC>
 __global__ __launch_bounds__(256) void absmax_kernel(DevProblem p, int64_t rows, WsHeader* hdr) {
-  const int64_t total = rows * p.cols;
   float m = 0.0f;
-  for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < total; k += (int64_t)gridDim.x * blockDim.x) {
-    float v = load_importance(p, k / p.cols, k % p.cols);
-    m = fmaxf(m, v);
+  if constexpr (VEC) {
+    const int64_t vpr = p.cols / 8;  // 8-weight vectors per row
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
+      for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < vpr; v += (int64_t)gridDim.x * blockDim.x) {
+        float w[8];
+        if (p.dtype == TSENOR_BF16) {
+          const uint4 raw = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned short*>(p.W) + r * p.ld + v * 8);
+          const unsigned int u[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            w[2 * k] = __uint_as_float(u[k] << 16);
+            w[2 * k + 1] = __uint_as_float(u[k] & 0xFFFF0000u);
+          }
+        } else {
+          const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.W) + r * p.ld + v * 8);
+          const float4 a = src[0], b = src[1];
+          w[0] = a.x, w[1] = a.y, w[2] = a.z, w[3] = a.w, w[4] = b.x, w[5] = b.y, w[6] = b.z, w[7] = b.w;
+        }
+        if (p.col_scale) {
+          const float4* cs = reinterpret_cast<const float4*>(p.col_scale + v * 8);
+          const float4 a = cs[0], b = cs[1];
+          const float c[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+          for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(w[k]) * c[k]);
+        } else {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(w[k]));
+        }
+      }
+    }
+  } else {
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y)
+      for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < p.cols; c += (int64_t)gridDim.x * blockDim.x)
+        m = fmaxf(m, load_importance(p, r, c));
   }
+  // one atomic per workgroup: thousands of atomics on one address would take longer than the reads
+  __shared__ float wave_max[4];
   for (int s = 1; s < kWave; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, kWave));
-  if ((threadIdx.x & (kWave - 1)) == 0) atomicMax(&hdr->max_bits, __float_as_uint(m));
+  if ((threadIdx.x & (kWave - 1)) == 0) wave_max[threadIdx.x / kWave] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    m = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+    atomicMax(&hdr->max_bits, __float_as_uint(m));
+  }
 }
 
 __global__ void fill_kernel(uint8_t* mask, int64_t total, uint8_t value) {
@@ -89,7 +129,7 @@ int validate(const tsenor_problem* p) {
   return TSENOR_OK;
 }
 
-template <int M, int L3>
+template <int M>
 int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char* ws, const WsLayout& l,
                hipStream_t stream, hipEvent_t* ev) {
   // ev (optional): TSENOR_NUM_STAGES + 1 events recorded at the stage boundaries
@@ -102,9 +142,16 @@ int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char
   unsigned int* accept = reinterpret_cast<unsigned int*>(ws + l.accept);
   init_kernel<<<1, 1, 0, stream>>>(hdr);
   if (dp.tau_mode == TSENOR_TAU_REL_MATRIX_MAX) {
-    const int64_t total = rows * dp.cols;
-    const int grid = (int)std::min<int64_t>((total + 256 * 8 - 1) / (256 * 8), 256 * 16);
-    absmax_kernel<<<grid, 256, 0, stream>>>(dp, rows, hdr);
+    const size_t esize = dp.dtype == TSENOR_BF16 ? 2 : 4;
+    const bool vec = dp.cols % 8 == 0 && reinterpret_cast<uintptr_t>(dp.W) % 16 == 0 && (dp.ld * esize) % 16 == 0 &&
+                     reinterpret_cast<uintptr_t>(dp.col_scale) % 16 == 0;
+    const int64_t per_row = vec ? dp.cols / 8 : dp.cols;
+    const unsigned gx = (unsigned)std::min<int64_t>((per_row + 255) / 256, 16);
+    const dim3 grid(gx, (unsigned)std::min<int64_t>(rows, std::max<unsigned>(1024 / gx, 1)));  // ~1024 workgroups
+    if (vec)
+      absmax_kernel<true><<<grid, 256, 0, stream>>>(dp, rows, hdr);
+    else
+      absmax_kernel<false><<<grid, 256, 0, stream>>>(dp, rows, hdr);
   }
   mark(1);
   constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
@@ -115,9 +162,9 @@ int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char
   greedy_kernel<M><<<(unsigned)((dp.nblocks + kWave - 1) / kWave), kWave, 0, stream>>>(order, dp.nblocks, dp.N,
                                                                                       accept, hdr);
   mark(3);
-  constexpr int G = kWave / L3;
-  finalize_kernel<M, L3>
-      <<<(unsigned)((dp.nblocks + G - 1) / G), kWave, 0, stream>>>(dp, order, accept, p.mask, hdr, p.stats_out);
+  constexpr int G = kWave / M;
+  const int wide = reinterpret_cast<uintptr_t>(p.mask) % 16 == 0;
+  finalize_kernel<M><<<(unsigned)((dp.nblocks + G - 1) / G), kWave, 0, stream>>>(dp, order, accept, p.mask, hdr, wide);
   if (p.stats_out) stats_kernel<<<1, 1, 0, stream>>>(hdr, p.stats_out);
   mark(4);
   return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
@@ -156,11 +203,11 @@ int run_one(const tsenor_problem& p, char* ws, hipStream_t stream, hipEvent_t* e
   dp.tau_mode = p.tau_mode;
   const WsLayout l = layout_of(p);
   switch (p.M) {
-    case 4: return launch_all<4, 16>(dp, p.rows, p, ws, l, stream, ev);
-    case 8: return launch_all<8, 64>(dp, p.rows, p, ws, l, stream, ev);
-    case 16: return launch_all<16, 64>(dp, p.rows, p, ws, l, stream, ev);
-    case 32: return launch_all<32, 64>(dp, p.rows, p, ws, l, stream, ev);
-    case 64: return launch_all<64, 64>(dp, p.rows, p, ws, l, stream, ev);
+    case 4: return launch_all<4>(dp, p.rows, p, ws, l, stream, ev);
+    case 8: return launch_all<8>(dp, p.rows, p, ws, l, stream, ev);
+    case 16: return launch_all<16>(dp, p.rows, p, ws, l, stream, ev);
+    case 32: return launch_all<32>(dp, p.rows, p, ws, l, stream, ev);
+    case 64: return launch_all<64>(dp, p.rows, p, ws, l, stream, ev);
   }
   return TSENOR_ERR_UNSUPPORTED;
 }

@@ -219,3 +219,116 @@ def test_side_stream(dev):
     s.synchronize()
     ref = oracle.mask(g["W_f32"], w.N, w.M, w.tau, w.iters, tau_mode=w.tau_mode)
     assert np.array_equal(res["mask"].cpu().numpy(), ref["mask"])
+
+
+# ----------------------------------------------------------------------------------------------------
+# Full-size workloads in the launch configuration bench.py times; the oracle checks sampled block-rows
+# (blocks are independent, Sec. 3.1) and the invariants are checked on the whole mask.
+# ----------------------------------------------------------------------------------------------------
+
+def _sample_block_rows(w, count):
+    nbr = w.rows // w.M
+    picks = sorted({0, nbr - 1, nbr // 2} | {int(x) for x in np.random.default_rng(w.seed).integers(0, nbr, count)})
+    return picks[:max(count, 3)]
+
+
+def _check_sampled(w, g, mask_host, plan_rows, sample, stats_host=None):
+    """mask_host: full mask; plan_rows: dict block-row -> plan rows (or None)."""
+    imp = oracle.importance(g["W_f32"], g["col_scale"])
+    te = oracle.tau_eff(imp, w.tau, w.tau_mode)          # matrix maximum over the whole matrix
+    assert exact.is_transposable_nm(mask_host, w.N, w.M)
+    identical = total = 0
+    for br in sample:
+        rows = slice(br * w.M, (br + 1) * w.M)
+        imp_s = np.ascontiguousarray(imp[rows])
+        log_S = oracle.dykstra(imp_s, w.N, w.M, te, w.iters)
+        m_ref, _ = oracle.round_plan(log_S, imp_s, w.N, w.M)
+        same = (exact.blocks(mask_host[rows], w.M) == exact.blocks(m_ref, w.M)).all(axis=(1, 2))
+        identical += int(same.sum())
+        total += same.size
+        if plan_rows is not None:
+            err = np.abs(plan_rows[br] - np.exp(log_S)).max()
+            assert err <= PLAN_ATOL, f"block-row {br}: plan differs by {err}"
+        kept_gpu = float((mask_host[rows] * imp_s.astype(np.float64)).sum())
+        kept_ref = float((m_ref * imp_s.astype(np.float64)).sum())
+        assert abs(kept_gpu - kept_ref) <= 1e-5 * kept_ref
+    assert identical >= 0.999 * total, f"{identical} of {total} sampled blocks identical"
+    return identical, total
+
+
+@pytest.mark.parametrize("name,nsample,want_plan", [("cfg2_8of16_4096", 16, True), ("cfg3_16of32_4096x14336", 8, True),
+                                                    ("cfg5_32of64_8192x28672", 3, False)])
+def test_full_size_sampled_parity(dev, name, nsample, want_plan):
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.CONFIGS[name]
+    print(f"[case] full size {w.name}: generating", flush=True)
+    g = synth.generate(w)
+    W, cs = _to_device(g, w, dev)
+    print("[case] running on the GPU", flush=True)
+    res = binding.solve(W, w.N, w.M, w.tau, w.iters, col_scale=cs, tau_mode=w.tau_mode, want_plan=want_plan,
+                        want_stats=True)
+    torch.cuda.synchronize()
+    sample = _sample_block_rows(w, nsample)
+    mask_host = res["mask"].cpu().numpy()
+    plan_rows = None
+    if want_plan:
+        plan_rows = {br: res["plan"][br * w.M:(br + 1) * w.M].cpu().numpy() for br in sample}
+    del res, W
+    torch.cuda.empty_cache()
+    print(f"[case] oracle on block-rows {sample}", flush=True)
+    identical, total = _check_sampled(w, g, mask_host, plan_rows, sample)
+    print(f"  {identical} of {total} sampled blocks identical", flush=True)
+
+
+def test_full_layer_batched_sampled_parity(dev):
+    # the seven projections of one 8B decoder layer through one tsenor_mask_batched call
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    ws = synth.layer_workloads(0)
+    gens, keep, probs, masks = [], [], [], []
+    for w in ws:
+        print(f"[case] layer matrix {w.name} {w.rows}x{w.cols}: generating", flush=True)
+        g = synth.generate(w)
+        W, cs = _to_device(g, w, dev)
+        m = torch.empty(W.shape, dtype=torch.uint8, device=dev)
+        gens.append(g)
+        keep += [W, cs]
+        masks.append(m)
+        probs.append(binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=m, col_scale=cs, tau_mode=w.tau_mode))
+    work = torch.empty(binding.tsenor_workspace_bytes(probs), dtype=torch.uint8, device=dev)
+    print("[case] running the batch on the GPU", flush=True)
+    binding.tsenor_mask_batched(probs, work)
+    torch.cuda.synchronize()
+    for w, g, m in zip(ws, gens, masks):
+        sample = _sample_block_rows(w, 2)
+        identical, total = _check_sampled(w, g, m.cpu().numpy(), None, sample)
+        print(f"  {w.name}: {identical} of {total} sampled blocks identical", flush=True)
+
+
+def test_unaligned_views(dev):
+    # W, col_scale and mask at addresses that rule out 16-byte vector loads / wide stores
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.Workload("unaligned_16of32", 64, 96, 16, 32, 0.005, 40, "bf16", "wanda", 93)
+    g = synth.generate(w)
+    W0, cs0 = _to_device(g, w, dev)
+    buf = torch.zeros((w.rows, w.cols + 8), dtype=torch.bfloat16, device=dev)
+    buf[:, 1:w.cols + 1] = W0
+    Wv = buf[:, 1:w.cols + 1]                               # 2-byte offset, ld = cols + 8
+    csb = torch.zeros(w.cols + 1, dtype=torch.float32, device=dev)
+    csb[1:] = cs0
+    mbuf = torch.zeros(w.rows * w.cols + 1, dtype=torch.uint8, device=dev)
+    mview = mbuf[1:].view(w.rows, w.cols)
+    p = binding.make_problem(Wv, w.N, w.M, w.tau, w.iters, mask=mview, col_scale=csb[1:], tau_mode=w.tau_mode)
+    work = torch.empty(binding.tsenor_workspace_bytes([p]), dtype=torch.uint8, device=dev)
+    binding.tsenor_mask_ex(p, work)
+    torch.cuda.synchronize()
+    ref = oracle.mask(g["W_f32"], w.N, w.M, w.tau, w.iters, col_scale=g["col_scale"], tau_mode=w.tau_mode)
+    assert np.array_equal(mview.cpu().numpy(), ref["mask"])
