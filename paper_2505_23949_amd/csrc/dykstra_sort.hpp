@@ -169,11 +169,13 @@ __device__ __forceinline__ void sort_ascending(double (&c)[E], int q) {
     } else {
       constexpr int lm = K / E - 1;
       const bool keep_min = (q & (K / E / 2)) == 0;
-      double o[E];
+      // position r meets the partner lane's position E-1-r; two registers at a time keeps this in place
 #pragma unroll
-      for (int r = 0; r < E; ++r) o[r] = lane_xor<lm>(c[E - 1 - r]);
-#pragma unroll
-      for (int r = 0; r < E; ++r) c[r] = ((c[r] < o[r]) == keep_min) ? c[r] : o[r];
+      for (int r = 0; r < E / 2; ++r) {
+        const double o_lo = lane_xor<lm>(c[E - 1 - r]), o_hi = lane_xor<lm>(c[r]);
+        c[r] = ((c[r] < o_lo) == keep_min) ? c[r] : o_lo;
+        c[E - 1 - r] = ((c[E - 1 - r] < o_hi) == keep_min) ? c[E - 1 - r] : o_hi;
+      }
     }
     sort_half_cleaners<E, LPB, K / 4>(c, q);
     sort_ascending<E, LPB, K * 2>(c, q);
@@ -275,6 +277,14 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
       for (int a = 0; a < OWN_R; ++a) R[a] = Nd * fast_rcp(fmax(R[a], 1e-300));
       all_gather_x<T, TH>(R);
       // projection onto C2 (line 4)
+      double Vc[TW];
+#pragma unroll
+      for (int b = 0; b < TW; ++b) {
+        Vc[b] = V[b];
+        // tiles too large to keep e: recompute it from an opaque copy of V, or the compiler keeps the
+        // row pass's values alive and spills them
+        if constexpr (!T::STORE_E) asm volatile("" : "+v"(Vc[b]));
+      }
 #pragma unroll
       for (int b = 0; b < TW; ++b) {
         double s = 0.0;
@@ -284,7 +294,7 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
           if constexpr (T::STORE_E)
             ev = e[a][b];
           else
-            ev = fmin(fmax((kap[a][b] * V[b]) * U[a], 0.0), 1.0);
+            ev = fmin(fmax((kap[a][b] * Vc[b]) * U[a], 0.0), 1.0);
           s = fma(ev, R[a], s);
         }
         C[b] = s;
