@@ -8,45 +8,82 @@
 
 namespace tsenor_dev {
 
+// Bit masks over the M columns (or rows) of a block.
+template <int M>
+using block_mask_t = typename std::conditional<(M > 32), unsigned long long, unsigned int>::type;
+
+template <class mask_t>
+__device__ __forceinline__ int mask_popc(mask_t v) {
+  if constexpr (sizeof(mask_t) == 8)
+    return __popcll((unsigned long long)v);
+  else
+    return __popc((unsigned int)v);
+}
+
 // Algorithm 2 lines 1-6: scan the entries of a block in sorted order and keep an entry while its row
-// and its column hold fewer than N.  One lane per block; bit t of the output says whether the t-th
-// entry of the order was kept.
+// and its column hold fewer than N.  The chain of M*M dependent steps runs with ONE LANE PER BLOCK, so
+// every lane of the wave does useful work; the state of a lane (M row masks, M column counters) lives in
+// LDS.  Output: the mask as M row bit masks per block (bit c of word r = S[r][c]).
 template <int M>
 __global__ __launch_bounds__(kWave) void greedy_kernel(const unsigned short* order, int64_t nblocks, int N,
-                                                       unsigned int* accept, WsHeader* hdr) {
-  constexpr int MM = M * M, WORDS = MM >= 32 ? MM / 32 : 1, PER_WORD = MM >= 32 ? 32 : MM;
-  __shared__ unsigned char cnt[2 * M][kWave];
+                                                       block_mask_t<M>* rowmask, WsHeader* hdr) {
+  using mask_t = block_mask_t<M>;
+  constexpr int MM = M * M;
+  __shared__ mask_t rowbits[M][kWave];
+  __shared__ unsigned char colcnt[M][kWave];
   const int lane = threadIdx.x;
   const int64_t blk = (int64_t)blockIdx.x * kWave + lane;
-  for (int k = 0; k < 2 * M; ++k) cnt[k][lane] = 0;
+  for (int k = 0; k < M; ++k) {
+    rowbits[k][lane] = 0;
+    colcnt[k][lane] = 0;
+  }
   int missing = 0;
   if (blk < nblocks) {
     const unsigned short* src = order + blk * MM;
     int placed = 0;
-    for (int w = 0; w < WORDS; ++w) {
-      unsigned int acc = 0;
-      for (int h = 0; h < PER_WORD; h += 8) {
-        const uint4 v = *reinterpret_cast<const uint4*>(src + w * PER_WORD + h);
-        const unsigned int pk[4] = {v.x, v.y, v.z, v.w};
+    const int need = N * M;
+    for (int h = 0; h < MM && placed < need; h += 8) {
+      const uint4 v = *reinterpret_cast<const uint4*>(src + h);
+      const unsigned int pk[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const unsigned int idx = (pk[u >> 1] >> ((u & 1) * 16)) & (unsigned)(MM - 1);
-          const unsigned int i = idx / M, j = idx % M;
-          const unsigned int ri = cnt[i][lane], cj = cnt[M + j][lane];
-          if (ri < (unsigned)N && cj < (unsigned)N) {
-            cnt[i][lane] = (unsigned char)(ri + 1);
-            cnt[M + j][lane] = (unsigned char)(cj + 1);
-            acc |= 1u << (h + u);
-            ++placed;
-          }
+      for (int u = 0; u < 8; ++u) {
+        const unsigned int idx = (pk[u >> 1] >> ((u & 1) * 16)) & (unsigned)(MM - 1);
+        const unsigned int i = idx / M, j = idx % M;
+        const mask_t rb = rowbits[i][lane];
+        const unsigned int cj = colcnt[j][lane];
+        if (mask_popc(rb) < N && cj < (unsigned)N) {
+          rowbits[i][lane] = rb | ((mask_t)1 << j);
+          colcnt[j][lane] = (unsigned char)(cj + 1);
+          ++placed;
         }
       }
-      accept[blk * WORDS + w] = acc;
     }
-    missing = N * M - placed;
+    for (int k = 0; k < M; ++k) rowmask[blk * M + k] = rowbits[k][lane];
+    missing = need - placed;
   }
   for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
   if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
+}
+
+// Transpose of an M x M bit matrix held as one M-bit row per lane (M consecutive lanes): afterwards the
+// lane that held row r holds column r.  log2(M) block-swap steps.
+template <int M, int S = M / 2, class mask_t>
+__device__ __forceinline__ mask_t bit_transpose(mask_t x, int ql) {
+  if constexpr (S >= 1) {
+    // bits whose index has bit S clear: S ones, S zeros, repeated
+    mask_t lowpat = 0;
+    for (int k = 0; k < M; ++k)
+      if (!(k & S)) lowpat |= (mask_t)1 << k;
+    mask_t other;
+    if constexpr (sizeof(mask_t) == 8)
+      other = (mask_t)__double_as_longlong(lane_xor<S>(__longlong_as_double((long long)x)));
+    else
+      other = (mask_t)lane_xor_i32<S>((int)x);
+    x = (ql & S) ? (mask_t)((x & ~lowpat) | ((other & ~lowpat) >> S)) : (mask_t)((x & lowpat) | ((other & lowpat) << S));
+    return bit_transpose<M, S / 2>(x, ql);
+  } else {
+    return x;
+  }
 }
 
 // Best candidate of Eq. (5) held by a lane: score, flat index i'*M+j' (MM = none).  Higher score wins,
@@ -75,11 +112,10 @@ __device__ __forceinline__ SwapBest group_best(SwapBest v) {
 // Algorithm 2 lines 7-13 and the mask write.  M lanes per block (lane r owns row r and column r of the
 // block as bit masks), 64/M blocks per wave, one wave per workgroup.
 template <int M>
-__global__ __launch_bounds__(kWave) void finalize_kernel(DevProblem p, const unsigned short* order,
-                                                         const unsigned int* accept, uint8_t* mask, WsHeader* hdr,
-                                                         int wide_store) {
-  using mask_t = typename std::conditional<(M > 32), unsigned long long, unsigned int>::type;
-  constexpr int MM = M * M, G = kWave / M, WORDS = MM >= 32 ? MM / 32 : 1, PER_WORD = MM >= 32 ? 32 : MM;
+__global__ __launch_bounds__(kWave) void finalize_kernel(DevProblem p, const block_mask_t<M>* rowmask, uint8_t* mask,
+                                                         WsHeader* hdr, int wide_store) {
+  using mask_t = block_mask_t<M>;
+  constexpr int MM = M * M, G = kWave / M;
   __shared__ float imp[G][MM];
   __shared__ mask_t rowm[G][M], colm[G][M];  // rowm[r] bit c == colm[c] bit r == S[r][c]
   const int lane = threadIdx.x, g = lane / M, ql = lane % M;
@@ -89,21 +125,14 @@ __global__ __launch_bounds__(kWave) void finalize_kernel(DevProblem p, const uns
   const int64_t r0 = (blk / p.bc) * M, c0 = (blk % p.bc) * M;
   const mask_t one = 1;
 
-  rowm[g][ql] = 0;
-  colm[g][ql] = 0;
-  __syncthreads();
-  // the mask greedy selection left: entry t of the order was kept iff bit t is set
-  for (int k = 0; k < M; ++k) {
-    const int pos = k * M + ql;
-    const unsigned int bit = (accept[blk * WORDS + pos / PER_WORD] >> (pos % PER_WORD)) & 1u;
-    if (bit) {
-      const int idx = order[blk * MM + pos] & (MM - 1);
-      atomicOr(&rowm[g][idx / M], one << (idx % M));
-      atomicOr(&colm[g][idx % M], one << (idx / M));
-    }
+  // the mask greedy selection left, and its transpose
+  {
+    const mask_t r = rowmask[blk * M + ql];
+    rowm[g][ql] = r;
+    colm[g][ql] = bit_transpose<M>(r, ql);
   }
   __syncthreads();
-  const auto popc = [](mask_t v) { return sizeof(mask_t) == 8 ? __popcll((unsigned long long)v) : __popc((unsigned int)v); };
+  const auto popc = [](mask_t v) { return mask_popc(v); };
   const unsigned long long gmask = (M == 64 ? ~0ull : ((1ull << M) - 1)) << (g * M);
   const bool any_short = __any(popc(rowm[g][ql]) < p.N);
   if (any_short) {

@@ -101,7 +101,8 @@ struct WsLayout {
   size_t header, order, accept, total;
 };
 
-inline int words_per_block(int M) { return M * M >= 32 ? M * M / 32 : 1; }
+// greedy's output: M row bit masks per block, 32-bit words up to M = 32, 64-bit for M = 64
+inline size_t rowmask_bytes_per_block(int M) { return (size_t)M * (M > 32 ? 8 : 4); }
 
 WsLayout layout_of(const tsenor_problem& p) {
   WsLayout l;
@@ -110,7 +111,7 @@ WsLayout layout_of(const tsenor_problem& p) {
   l.header = 0;
   l.order = kAlign;
   l.accept = l.order + align_up(elems * sizeof(unsigned short));
-  l.total = l.accept + align_up(nblocks * words_per_block(p.M) * sizeof(unsigned int));
+  l.total = l.accept + align_up(nblocks * rowmask_bytes_per_block(p.M));
   return l;
 }
 
@@ -139,7 +140,7 @@ int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char
   mark(0);
   WsHeader* hdr = reinterpret_cast<WsHeader*>(ws + l.header);
   unsigned short* order = reinterpret_cast<unsigned short*>(ws + l.order);
-  unsigned int* accept = reinterpret_cast<unsigned int*>(ws + l.accept);
+  block_mask_t<M>* accept = reinterpret_cast<block_mask_t<M>*>(ws + l.accept);
   init_kernel<<<1, 1, 0, stream>>>(hdr);
   if (dp.tau_mode == TSENOR_TAU_REL_MATRIX_MAX) {
     const size_t esize = dp.dtype == TSENOR_BF16 ? 2 : 4;
@@ -164,7 +165,7 @@ int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char
   mark(3);
   constexpr int G = kWave / M;
   const int wide = reinterpret_cast<uintptr_t>(p.mask) % 16 == 0;
-  finalize_kernel<M><<<(unsigned)((dp.nblocks + G - 1) / G), kWave, 0, stream>>>(dp, order, accept, p.mask, hdr, wide);
+  finalize_kernel<M><<<(unsigned)((dp.nblocks + G - 1) / G), kWave, 0, stream>>>(dp, accept, p.mask, hdr, wide);
   if (p.stats_out) stats_kernel<<<1, 1, 0, stream>>>(hdr, p.stats_out);
   mark(4);
   return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
