@@ -28,6 +28,7 @@ TSENOR_TAU_ABSOLUTE = 0
 TSENOR_TAU_REL_MATRIX_MAX = 1
 TSENOR_FLAG_STRICT_PAPER = 1 << 0
 TSENOR_FLAG_COLS_FIRST = 1 << 1
+TSENOR_FLAG_FP32_ITERATIONS = 1 << 2
 
 EXPORTS = (
     "tsenor_workspace_bytes", "tsenor_mask_ex", "tsenor_mask_batched", "tsenor_mask", "tsenor_mask_ex_profile",

@@ -4,13 +4,22 @@
 // log S = min(A, 0) and log Q = max(A, 0) after every iteration, and one iteration adds a row term
 // and a column term to A.  So A = K + f_i + g_j with K = tau_eff * importance: the whole Dykstra
 // state of a block is K plus 2M potentials.  The kernel keeps kappa = exp(K - max K) and the scalings
-// U_i = exp(f_i), V_j = exp(g_j) in double precision and iterates
+// U_i = exp(f_i), V_j = exp(g_j) and iterates
 //     e_ij = min(kappa_ij V_j U_i, 1);   R_i = N / sum_j e_ij;   C_j = N / sum_i e_ij R_i;
 //     U_i *= R_i;   V_j *= C_j
 // which is lines 3-6 of Algorithm 1 in exact arithmetic: the row scaling acts on the plan capped by
 // the previous iteration, the column scaling on the row-scaled plan, and the cap with its dual is the
 // min(., 1) at the top of the next pass (App. A.2 listing, same order of operations).  Four
-// double-precision operations per entry and iteration and no transcendental in the loop.
+// operations per entry and iteration and no transcendental in the loop.
+//
+// Precision.  Default: everything in double (MI355X issues fp64 vector operations at 16 lanes/clk/SIMD),
+// which reproduces a double-precision reference to ~1e-13.  FAST: the first kWarmIters iterations in
+// double, then the loop in fp32 (twice the issue rate) on kappa32 = fl32(kappa U V) with fp32 scalings
+// relative to the double ones.  fp32 has 8 exponent bits, so every kChunk iterations the relative
+// scalings are checked and, when one has drifted past 2^+-kDriftBits, folded back into the double ones
+// and kappa32 is rebuilt from the double kappa kept in LDS.  Entries are clamped to [2^-120, 2^80] when
+// they are rebuilt; within the drift bound (2^+-80 for a product of a row and a column scaling) a
+// clamped entry is still >= 1 (capped) or <= 2^-40 (nothing).
 //
 // Layout.  A block is spread over LPB = GX*GY lanes as a GY x GX grid of TH x TW register tiles
 // (TH = M/GY rows, TW = M/GX columns); a wave holds 64/LPB blocks.  Row sums are reduced across the GX
@@ -26,6 +35,9 @@ namespace tsenor_dev {
 
 constexpr double kMinLogKernel = -700.0;  // exp(-700) is still a normal double
 constexpr int kIdxBits = 12;              // flat index within a block: up to 64*64 entries
+constexpr int kWarmIters = 8;             // FAST: iterations done in double before switching to fp32
+constexpr int kChunk = 8;                 // FAST: iterations between range checks of the fp32 scalings
+constexpr int kDriftBits = 40;            // FAST: fold the fp32 scalings back beyond 2^+-kDriftBits
 
 constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 
@@ -60,60 +72,71 @@ struct Tiling<32> {
 };
 template <>
 struct Tiling<64> {
-  static constexpr int NX = 3, NY = 3;  // 64 lanes per block, 8 x 8 tiles; too large to hold e as well
+  static constexpr int NX = 3, NY = 3;  // 64 lanes per block, 8 x 8 tiles; too large to hold e as doubles
   static constexpr int XM[3] = {7, 3, 1}, YM[3] = {8, 16, 32};
   static constexpr bool STORE_E = false;
 };
 
-// 1/d to double precision: hardware estimate plus two Newton steps.
+// 1/d: hardware estimate plus Newton steps (two for double: the estimate has ~24 bits; one for float).
 __device__ __forceinline__ double fast_rcp(double d) {
   double x = __builtin_amdgcn_rcp(d);
   x = fma(fma(-d, x, 1.0), x, x);
   x = fma(fma(-d, x, 1.0), x, x);
   return x;
 }
+__device__ __forceinline__ float fast_rcp(float d) {
+  float x = __builtin_amdgcn_rcpf(d);
+  x = fmaf(fmaf(-d, x, 1.0f), x, x);
+  return x;
+}
+__device__ __forceinline__ double clamp01(double x) { return fmin(fmax(x, 0.0), 1.0); }
+__device__ __forceinline__ float clamp01(float x) { return fminf(fmaxf(x, 0.0f), 1.0f); }
+__device__ __forceinline__ double vmax(double a, double b) { return fmax(a, b); }
+__device__ __forceinline__ float vmax(float a, float b) { return fmaxf(a, b); }
+__device__ __forceinline__ double vfma(double a, double b, double c) { return fma(a, b, c); }
+__device__ __forceinline__ float vfma(float a, float b, float c) { return fmaf(a, b, c); }
 
 // Recursive halving over the lanes of a lane-row.  v[0..TH): partial sums, register a <-> tile row
 // a ^ (gx << SH).  Afterwards v[0 .. TH >> NX) hold complete sums.
-template <class T, int TH, int S = 0>
-__device__ __forceinline__ void reduce_scatter_x(double (&v)[TH]) {
+template <class T, class real, int TH, int S = 0>
+__device__ __forceinline__ void reduce_scatter_x(real (&v)[TH]) {
   if constexpr (S < T::NX) {
     constexpr int SH = ilog2(TH) - T::NX;
     constexpr int h = TH >> (S + 1);
     constexpr int am = (T::XM[S] << SH) & (2 * h - 1);  // register index of the partner's matching value
 #pragma unroll
     for (int a = 0; a < h; ++a) v[a] += lane_xor<T::XM[S]>(v[a ^ am]);
-    reduce_scatter_x<T, TH, S + 1>(v);
+    reduce_scatter_x<T, real, TH, S + 1>(v);
   }
 }
-template <class T, int TH, int S = T::NX - 1>
-__device__ __forceinline__ void all_gather_x(double (&v)[TH]) {
+template <class T, class real, int TH, int S = T::NX - 1>
+__device__ __forceinline__ void all_gather_x(real (&v)[TH]) {
   if constexpr (S >= 0) {
     constexpr int SH = ilog2(TH) - T::NX;
     constexpr int h = TH >> (S + 1);
     constexpr int am = (T::XM[S] << SH) & (2 * h - 1);
 #pragma unroll
     for (int a = 0; a < h; ++a) v[a ^ am] = lane_xor<T::XM[S]>(v[a]);
-    all_gather_x<T, TH, S - 1>(v);
+    all_gather_x<T, real, TH, S - 1>(v);
   }
 }
 // The same over the lanes of a lane-column; step s pairs lanes that differ in lane bit YM[s].
-template <class T, int TW, int S = 0>
-__device__ __forceinline__ void reduce_scatter_y(double (&v)[TW]) {
+template <class T, class real, int TW, int S = 0>
+__device__ __forceinline__ void reduce_scatter_y(real (&v)[TW]) {
   if constexpr (S < T::NY) {
     constexpr int h = TW >> (S + 1);
 #pragma unroll
     for (int b = 0; b < h; ++b) v[b] += lane_xor<T::YM[S]>(v[b + h]);
-    reduce_scatter_y<T, TW, S + 1>(v);
+    reduce_scatter_y<T, real, TW, S + 1>(v);
   }
 }
-template <class T, int TW, int S = T::NY - 1>
-__device__ __forceinline__ void all_gather_y(double (&v)[TW]) {
+template <class T, class real, int TW, int S = T::NY - 1>
+__device__ __forceinline__ void all_gather_y(real (&v)[TW]) {
   if constexpr (S >= 0) {
     constexpr int h = TW >> (S + 1);
 #pragma unroll
     for (int b = 0; b < h; ++b) v[b + h] = lane_xor<T::YM[S]>(v[b]);
-    all_gather_y<T, TW, S - 1>(v);
+    all_gather_y<T, real, TW, S - 1>(v);
   }
 }
 // register offset of a lane along y: lane bit YM[s] set <-> register bit log2(TW >> (s+1))
@@ -125,6 +148,110 @@ __device__ __forceinline__ int reg_xor_y(int q) {
     return 0;
 }
 
+// One iteration of Algorithm 1 (lines 3-6) on the register tile of this lane.  `floor_` bounds the sums
+// from below (keeps the scalings finite on degenerate input).  STORE keeps the capped entries of the row
+// pass for the column pass; otherwise they are recomputed from an opaque copy of V (for tiles too large
+// to hold twice: without the copy the compiler keeps the row pass's values alive and spills them).
+template <class T, bool STORE, class real, int TH, int TW>
+__device__ __forceinline__ void dykstra_iteration(const real (&kap)[TH][TW], real (&U)[TH], real (&V)[TW], real Nd,
+                                                  real floor_) {
+  constexpr int OWN_R = TH >> T::NX, OWN_C = TW >> T::NY;
+  real e[STORE ? TH : 1][STORE ? TW : 1];
+  real R[TH], C[TW];
+  // projection onto C1 (line 3) of the plan capped by the previous iteration
+#pragma unroll
+  for (int a = 0; a < TH; ++a) {
+    real s = 0;
+#pragma unroll
+    for (int b = 0; b < TW; ++b) {
+      const real ev = clamp01((kap[a][b] * V[b]) * U[a]);
+      if constexpr (STORE) e[a][b] = ev;
+      s += ev;
+    }
+    R[a] = s;
+  }
+  reduce_scatter_x<T, real, TH>(R);
+#pragma unroll
+  for (int a = 0; a < OWN_R; ++a) R[a] = Nd * fast_rcp(vmax(R[a], floor_));
+  all_gather_x<T, real, TH>(R);
+  // projection onto C2 (line 4)
+  real Vc[TW];
+#pragma unroll
+  for (int b = 0; b < TW; ++b) {
+    Vc[b] = V[b];
+    if constexpr (!STORE) asm volatile("" : "+v"(Vc[b]));
+  }
+#pragma unroll
+  for (int b = 0; b < TW; ++b) {
+    real s = 0;
+#pragma unroll
+    for (int a = 0; a < TH; ++a) {
+      real ev;
+      if constexpr (STORE)
+        ev = e[a][b];
+      else
+        ev = clamp01((kap[a][b] * Vc[b]) * U[a]);
+      s = vfma(ev, R[a], s);
+    }
+    C[b] = s;
+  }
+  reduce_scatter_y<T, real, TW>(C);
+#pragma unroll
+  for (int b = 0; b < OWN_C; ++b) C[b] = Nd * fast_rcp(vmax(C[b], floor_));
+  all_gather_y<T, real, TW>(C);
+#pragma unroll
+  for (int a = 0; a < TH; ++a) U[a] *= R[a];
+#pragma unroll
+  for (int b = 0; b < TW; ++b) V[b] *= C[b];
+  // lines 5-6 (cap and dual update) are the clamp at the top of the next pass
+}
+
+// The same iteration in single precision, arranged so that every per-entry operation is a plain two- or
+// three-operand fp32 instruction (the clamp output modifier needs the long encoding, which issues at half
+// the fp32 rate).  With e'_ij = min(kappa_ij V_j, 1/U_i) = e_ij / U_i:
+//     sum_j e'_ij = (sum_j e_ij) / U_i,  so  U_i R_i = N / sum_j e'_ij   and   sum_i e_ij R_i = sum_i e'_ij (U_i R_i).
+// U, Uinv: scaling of every tile row and its reciprocal; V: scaling of every tile column.  A row scaling
+// grows by at most 2^10 per iteration (keeps everything finite on degenerate input).
+template <class T, int TH, int TW>
+__device__ __forceinline__ void dykstra_iteration_f32(const float (&kap)[TH][TW], float (&U)[TH], float (&Uinv)[TH],
+                                                      float (&V)[TW], float Nf) {
+  constexpr int OWN_R = TH >> T::NX, OWN_C = TW >> T::NY;
+  float e[TH][TW], S[TH], C[TW];
+#pragma unroll
+  for (int a = 0; a < TH; ++a) {
+#pragma unroll
+    for (int b = 0; b < TW; ++b) {
+      e[a][b] = fminf(kap[a][b] * V[b], Uinv[a]);
+      S[a] = b == 0 ? e[a][b] : S[a] + e[a][b];
+    }
+  }
+  reduce_scatter_x<T, float, TH>(S);
+  float Un[TH];
+#pragma unroll
+  for (int a = 0; a < OWN_R; ++a) {
+    Un[a] = fminf(Nf * fast_rcp(S[a]), U[a] * 1024.0f);  // new scaling of an owned row
+    S[a] = fast_rcp(Un[a]);                              // and its reciprocal
+  }
+  all_gather_x<T, float, TH>(Un);
+  all_gather_x<T, float, TH>(S);
+#pragma unroll
+  for (int a = 0; a < TH; ++a) {
+    U[a] = Un[a];
+    Uinv[a] = S[a];
+  }
+#pragma unroll
+  for (int b = 0; b < TW; ++b) {
+#pragma unroll
+    for (int a = 0; a < TH; ++a) C[b] = a == 0 ? e[a][b] * U[a] : fmaf(e[a][b], U[a], C[b]);
+  }
+  reduce_scatter_y<T, float, TW>(C);
+#pragma unroll
+  for (int b = 0; b < OWN_C; ++b) C[b] = Nf * fast_rcp(fmaxf(C[b], Nf * 0x1p-10f));
+  all_gather_y<T, float, TW>(C);
+#pragma unroll
+  for (int b = 0; b < TW; ++b) V[b] *= C[b];
+}
+
 __device__ __forceinline__ void compare_exchange(double& lo, double& hi) {
   const double a = fmin(lo, hi), b = fmax(lo, hi);
   lo = a;
@@ -134,7 +261,6 @@ __device__ __forceinline__ void compare_exchange(double& lo, double& hi) {
 // Ascending bitonic sort of E*LPB distinct positive doubles spread over LPB lanes (position q*E + r).
 // Every merge starts with the mirrored compare (position p against p ^ (k-1)), after which the smaller
 // key always belongs at the lower position, so no direction flags are needed.
-
 template <int E, int LPB, int J>
 __device__ __forceinline__ void sort_half_cleaners(double (&c)[E], int q) {
   if constexpr (J >= 1) {
@@ -182,15 +308,24 @@ __device__ __forceinline__ void sort_ascending(double (&c)[E], int q) {
   }
 }
 
-template <int M>
-__global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, const WsHeader* hdr, unsigned short* order,
-                                                            double* plan_out, double* tau_eff_out) {
+template <int M, bool FAST>
+struct DykstraLaunch {
+  // FAST keeps a double copy of kappa in LDS (E x 64 doubles per wave); M = 64 uses two-wave workgroups
+  // so that two workgroups still fit a CU
+  static constexpr int kWavesPerGroup = (FAST && M == 64) ? 2 : 4;
+  static constexpr int kThreads = kWavesPerGroup * kWave;
+};
+
+template <int M, bool FAST>
+__global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), 2) void dykstra_sort_kernel(
+    DevProblem p, const WsHeader* hdr, unsigned short* order, double* plan_out, double* tau_eff_out) {
   using T = Tiling<M>;
   constexpr int GX = 1 << T::NX, GY = 1 << T::NY, TH = M / GY, TW = M / GX, LPB = GX * GY, BPW = kWave / LPB,
-                E = TH * TW, OWN_R = TH / GX, OWN_C = TW / GY, SHX = ilog2(TH) - T::NX;
+                E = TH * TW, SHX = ilog2(TH) - T::NX, WPG = DykstraLaunch<M, FAST>::kWavesPerGroup;
   static_assert(TH >= GX && TW >= GY, "every lane must end a reduce-scatter with at least one sum");
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+  __shared__ double kap_lds[FAST ? WPG : 1][FAST ? E : 1][FAST ? kWave : 1];
+  const int lane = threadIdx.x & (kWave - 1), wave_in_group = threadIdx.x / kWave;
+  const int64_t wave = (int64_t)blockIdx.x * WPG + wave_in_group;
   const int q = lane % LPB, gx = q % GX, gy = q / GX;
   int64_t blk = wave * BPW + lane / LPB;
   const bool active = blk < p.nblocks;
@@ -247,6 +382,7 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
 #pragma unroll
       for (int b = 0; b < TW; ++b) {
         kap[a][b] = exp(fmax(kap[a][b] - mx, kMinLogKernel));
+        if constexpr (FAST) kap_lds[wave_in_group][a * TW + b][lane] = kap[a][b];
         __builtin_amdgcn_sched_barrier(0);  // one exp at a time: interleaving them only costs registers
       }
 
@@ -257,61 +393,53 @@ __global__ __launch_bounds__(256, 2) void dykstra_sort_kernel(DevProblem p, cons
 #pragma unroll
     for (int b = 0; b < TW; ++b) V[b] = 1.0;
 
-    for (int t = 0; t < p.T; ++t) {
-      double e[T::STORE_E ? TH : 1][T::STORE_E ? TW : 1];
-      double R[TH], C[TW];
-      // projection onto C1 (Algorithm 1 line 3) of the plan capped by the previous iteration
+    const int t_double = FAST ? (p.T < kWarmIters ? p.T : kWarmIters) : p.T;
+    for (int t = 0; t < t_double; ++t) dykstra_iteration<T, T::STORE_E>(kap, U, V, Nd, 1e-300);
+
+    if constexpr (FAST) {
+      if (p.T > t_double) {
+        // fp32 phase: kap32 = fl32(kap U V), scalings U32, V32 relative to the double ones
+        float kap32[TH][TW], U32[TH], Uinv32[TH], V32[TW];
+        const float Nf = (float)p.N;
+        const float hi = __builtin_ldexpf(1.0f, kDriftBits), lo = __builtin_ldexpf(1.0f, -kDriftBits);
+        auto rebuild = [&]() {
 #pragma unroll
-      for (int a = 0; a < TH; ++a) {
-        double s = 0.0;
+          for (int a = 0; a < TH; ++a)
 #pragma unroll
-        for (int b = 0; b < TW; ++b) {
-          const double ev = fmin(fmax((kap[a][b] * V[b]) * U[a], 0.0), 1.0);
-          if constexpr (T::STORE_E) e[a][b] = ev;
-          s += ev;
+            for (int b = 0; b < TW; ++b) {
+              const double full = (kap_lds[wave_in_group][a * TW + b][lane] * V[b]) * U[a];
+              kap32[a][b] = (float)fmin(fmax(full, 0x1p-120), 0x1p80);
+            }
+#pragma unroll
+          for (int a = 0; a < TH; ++a) U32[a] = Uinv32[a] = 1.0f;
+#pragma unroll
+          for (int b = 0; b < TW; ++b) V32[b] = 1.0f;
+        };
+        rebuild();
+        for (int t = t_double; t < p.T;) {
+          const int stop = (p.T - t > kChunk) ? t + kChunk : p.T;
+          for (; t < stop; ++t) dykstra_iteration_f32<T>(kap32, U32, Uinv32, V32, Nf);
+          float mxs = U32[0], mns = U32[0];
+#pragma unroll
+          for (int a = 1; a < TH; ++a) mxs = fmaxf(mxs, U32[a]), mns = fminf(mns, U32[a]);
+#pragma unroll
+          for (int b = 0; b < TW; ++b) mxs = fmaxf(mxs, V32[b]), mns = fminf(mns, V32[b]);
+          // wave-uniform: fold the fp32 scalings into the double ones when any lane's have drifted
+          if (t < p.T && __any(!(mxs < hi && mns > lo))) {
+#pragma unroll
+            for (int a = 0; a < TH; ++a) U[a] *= (double)U32[a];
+#pragma unroll
+            for (int b = 0; b < TW; ++b) V[b] *= (double)V32[b];
+            rebuild();
+          }
         }
-        R[a] = s;
+#pragma unroll
+        for (int a = 0; a < TH; ++a) U[a] *= (double)U32[a];
+#pragma unroll
+        for (int b = 0; b < TW; ++b) V[b] *= (double)V32[b];
       }
-      reduce_scatter_x<T, TH>(R);
-#pragma unroll
-      for (int a = 0; a < OWN_R; ++a) R[a] = Nd * fast_rcp(fmax(R[a], 1e-300));
-      all_gather_x<T, TH>(R);
-      // projection onto C2 (line 4)
-      double Vc[TW];
-#pragma unroll
-      for (int b = 0; b < TW; ++b) {
-        Vc[b] = V[b];
-        // tiles too large to keep e: recompute it from an opaque copy of V, or the compiler keeps the
-        // row pass's values alive and spills them
-        if constexpr (!T::STORE_E) asm volatile("" : "+v"(Vc[b]));
-      }
-#pragma unroll
-      for (int b = 0; b < TW; ++b) {
-        double s = 0.0;
-#pragma unroll
-        for (int a = 0; a < TH; ++a) {
-          double ev;
-          if constexpr (T::STORE_E)
-            ev = e[a][b];
-          else
-            ev = fmin(fmax((kap[a][b] * Vc[b]) * U[a], 0.0), 1.0);
-          s = fma(ev, R[a], s);
-        }
-        C[b] = s;
-      }
-      reduce_scatter_y<T, TW>(C);
-#pragma unroll
-      for (int b = 0; b < OWN_C; ++b) C[b] = Nd * fast_rcp(fmax(C[b], 1e-300));
-      all_gather_y<T, TW>(C);
-#pragma unroll
-      for (int a = 0; a < TH; ++a) U[a] *= R[a];
-#pragma unroll
-      for (int b = 0; b < TW; ++b) V[b] *= C[b];
-      // lines 5-6 (cap and dual update) are the min(., 1) at the top of the next pass
     }
 
-    // fresh copies of the lane offsets: addresses are recomputed here rather than kept alive in
-    // registers across the iteration loop
     const int rx2 = fresh(rx), ry2 = fresh(ry);
     double lu[TH], lv[TW];
 #pragma unroll

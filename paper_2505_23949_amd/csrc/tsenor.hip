@@ -120,7 +120,7 @@ int validate(const tsenor_problem* p) {
   if (p->M != 4 && p->M != 8 && p->M != 16 && p->M != 32 && p->M != 64) return TSENOR_ERR_UNSUPPORTED;
   if (p->dtype != TSENOR_F32 && p->dtype != TSENOR_BF16) return TSENOR_ERR_UNSUPPORTED;
   if (p->tau_mode != TSENOR_TAU_ABSOLUTE && p->tau_mode != TSENOR_TAU_REL_MATRIX_MAX) return TSENOR_ERR_UNSUPPORTED;
-  if (p->flags & ~(uint32_t)(TSENOR_FLAG_STRICT_PAPER | TSENOR_FLAG_COLS_FIRST)) return TSENOR_ERR_UNSUPPORTED;
+  if (p->flags & ~(uint32_t)(TSENOR_FLAG_STRICT_PAPER | TSENOR_FLAG_COLS_FIRST | TSENOR_FLAG_FP32_ITERATIONS)) return TSENOR_ERR_UNSUPPORTED;
   if (p->rows <= 0 || p->cols <= 0 || p->rows % p->M || p->cols % p->M || p->ld < p->cols) return TSENOR_ERR_SHAPE;
   if (p->rows > (int64_t)1 << 31 || p->cols > (int64_t)1 << 31 || p->rows * p->cols > (int64_t)1 << 40)
     return TSENOR_ERR_SHAPE;
@@ -157,8 +157,15 @@ int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char
   mark(1);
   constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
   const int64_t waves = (dp.nblocks + BPW - 1) / BPW;
-  dykstra_sort_kernel<M>
-      <<<(unsigned)((waves + 3) / 4), 256, 0, stream>>>(dp, hdr, order, p.plan_out, p.tau_eff_out);
+  if (p.flags & TSENOR_FLAG_FP32_ITERATIONS) {
+    using L = DykstraLaunch<M, true>;
+    dykstra_sort_kernel<M, true><<<(unsigned)((waves + L::kWavesPerGroup - 1) / L::kWavesPerGroup), L::kThreads, 0,
+                                   stream>>>(dp, hdr, order, p.plan_out, p.tau_eff_out);
+  } else {
+    using L = DykstraLaunch<M, false>;
+    dykstra_sort_kernel<M, false><<<(unsigned)((waves + L::kWavesPerGroup - 1) / L::kWavesPerGroup), L::kThreads, 0,
+                                    stream>>>(dp, hdr, order, p.plan_out, p.tau_eff_out);
+  }
   mark(2);
   greedy_kernel<M><<<(unsigned)((dp.nblocks + kWave - 1) / kWave), kWave, 0, stream>>>(order, dp.nblocks, dp.N,
                                                                                       accept, hdr);

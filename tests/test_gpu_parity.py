@@ -332,3 +332,68 @@ def test_unaligned_views(dev):
     torch.cuda.synchronize()
     ref = oracle.mask(g["W_f32"], w.N, w.M, w.tau, w.iters, col_scale=g["col_scale"], tau_mode=w.tau_mode)
     assert np.array_equal(mview.cpu().numpy(), ref["mask"])
+
+
+# ----------------------------------------------------------------------------------------------------
+# TSENOR_FLAG_FP32_ITERATIONS: iterations after the eighth in single precision.  Bars as given for an
+# fp32 kernel against the double oracle: plan within 1e-4 absolute, masks identical on >= 99.9 % of
+# blocks, retained importance within 1e-5 relative, invariants exact.
+# ----------------------------------------------------------------------------------------------------
+
+FP32_PLAN_ATOL = 1e-4
+
+FP32_CASES = [
+    synth.CONFIGS["cfg1_2of4_512"],
+    synth.CONFIGS["cfg2_8of16_4096"].scaled(512, 1024),
+    synth.CONFIGS["cfg3_16of32_4096x14336"].scaled(160, 352),
+    synth.CONFIGS["cfg3_16of32_4096x14336"].scaled(1024, 2048),
+    synth.CONFIGS["cfg5_32of64_8192x28672"].scaled(192, 320),
+    synth.Workload("m8_3of8_bf16", 64, 256, 3, 8, 0.01, 100, "bf16", "wanda", 78),
+    synth.Workload("m32_few_iters", 64, 96, 16, 32, 0.005, 5, "f32", "normal", 82),      # T below the warm-up
+    synth.Workload("m32_nine_iters", 64, 96, 16, 32, 0.005, 9, "f32", "normal", 83),     # one fp32 iteration
+    synth.Workload("m16_hard", 128, 128, 8, 16, 0.0015, 300, "f32", "student_t", 84),    # logits up to 667
+]
+
+
+@pytest.mark.parametrize("w", FP32_CASES, ids=lambda w: w.name)
+def test_parity_fp32_iterations(dev, w):
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    g = synth.generate(w)
+    W, cs = _to_device(g, w, dev)
+    print(f"[case] fp32 iterations {w.name} {w.rows}x{w.cols} {w.N}:{w.M} T={w.iters}", flush=True)
+    res = binding.solve(W, w.N, w.M, w.tau, w.iters, col_scale=cs, tau_mode=w.tau_mode,
+                        flags=binding.TSENOR_FLAG_FP32_ITERATIONS, want_plan=True, want_stats=True)
+    torch.cuda.synchronize()
+    ref = oracle.mask(g["W_f32"], w.N, w.M, w.tau, w.iters, col_scale=g["col_scale"], tau_mode=w.tau_mode,
+                      return_plan=True)
+    mask, plan = res["mask"].cpu().numpy(), res["plan"].cpu().numpy()
+    err = np.abs(plan - np.exp(ref["log_S"])).max()
+    assert err <= FP32_PLAN_ATOL, f"plan differs by {err}"
+    assert exact.is_transposable_nm(mask, w.N, w.M)
+    same = (exact.blocks(mask, w.M) == exact.blocks(ref["mask"], w.M)).all(axis=(1, 2))
+    assert same.mean() >= 0.999, f"only {same.mean():.5f} of blocks identical"
+    imp = oracle.importance(g["W_f32"], g["col_scale"]).astype(np.float64)
+    kept_gpu, kept_ref = float((mask * imp).sum()), float((ref["mask"] * imp).sum())
+    assert abs(kept_gpu - kept_ref) <= 1e-5 * kept_ref
+    if same.all():
+        assert np.array_equal(res["stats"].cpu().numpy(), ref["stats"])
+    print(f"  identical blocks {same.mean():.5f} ({int((~same).sum())} differ), max plan error {err:.3e}", flush=True)
+
+
+def test_full_size_sampled_parity_fp32_iterations(dev):
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.CONFIGS["cfg3_16of32_4096x14336"]
+    g = synth.generate(w)
+    W, cs = _to_device(g, w, dev)
+    res = binding.solve(W, w.N, w.M, w.tau, w.iters, col_scale=cs, tau_mode=w.tau_mode,
+                        flags=binding.TSENOR_FLAG_FP32_ITERATIONS)
+    torch.cuda.synchronize()
+    sample = _sample_block_rows(w, 8)
+    identical, total = _check_sampled(w, g, res["mask"].cpu().numpy(), None, sample)
+    print(f"  fp32 iterations: {identical} of {total} sampled blocks identical", flush=True)
