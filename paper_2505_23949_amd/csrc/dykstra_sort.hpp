@@ -166,7 +166,7 @@ __device__ __forceinline__ void dykstra_iteration(const real (&kap)[TH][TW], rea
     for (int b = 0; b < TW; ++b) {
       const real ev = clamp01((kap[a][b] * V[b]) * U[a]);
       if constexpr (STORE) e[a][b] = ev;
-      s += ev;
+      s = b == 0 ? ev : s + ev;  // (0 + x is not a no-op for the compiler: it would keep the add)
     }
     R[a] = s;
   }

