@@ -316,7 +316,9 @@ struct DykstraLaunch {
   static constexpr int kThreads = kWavesPerGroup * kWave;
 };
 
-template <int M, bool FAST>
+// ZERO_T: the instantiation for T = 0 (no iterations, keys are K itself).  It is a template parameter
+// rather than a branch because keeping both paths in one kernel costs the iterating path ~40 registers.
+template <int M, bool FAST, bool ZERO_T = false>
 __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), 2) void dykstra_sort_kernel(
     DevProblem p, const WsHeader* hdr, unsigned short* order, double* plan_out, double* tau_eff_out) {
   using T = Tiling<M>;
@@ -349,19 +351,31 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), 2) void dykstra
 
   double kap[TH][TW];
   double mx = 0.0;
+  {
+    float imp[TH][TW];
 #pragma unroll
-  for (int a = 0; a < TH; ++a)
+    for (int a = 0; a < TH; ++a) {
 #pragma unroll
-    for (int b = 0; b < TW; ++b) {
-      const int ri = gy * TH + (a ^ rx), cj = gx * TW + (b ^ ry);
-      const float imp = load_importance(p, r0 + mat_row(ri, cj), c0 + mat_col(ri, cj));
-      kap[a][b] = tau_eff * (double)imp;  // K of Algorithm 1 line 1
-      mx = fmax(mx, kap[a][b]);
+      for (int b = 0; b < TW; ++b) {
+        const int ri = gy * TH + (a ^ rx), cj = gx * TW + (b ^ ry);
+        imp[a][b] = load_importance(p, r0 + mat_row(ri, cj), c0 + mat_col(ri, cj));
+      }
+      // one tile row of loads at a time: scheduling all address computations first costs more registers
+      // than the kernel has
+      __builtin_amdgcn_sched_barrier(0);
     }
+#pragma unroll
+    for (int a = 0; a < TH; ++a)
+#pragma unroll
+      for (int b = 0; b < TW; ++b) {
+        kap[a][b] = tau_eff * (double)imp[a][b];  // K of Algorithm 1 line 1
+        mx = fmax(mx, kap[a][b]);
+      }
+  }
   mx = group_max<LPB>(mx);
 
   double c[E];  // sort keys
-  if (p.T == 0) {
+  if constexpr (ZERO_T) {
     // no iterations: the greedy order is descending K itself
     const int rx0 = fresh(rx), ry0 = fresh(ry);
 #pragma unroll

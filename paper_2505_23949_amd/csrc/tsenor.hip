@@ -157,7 +157,11 @@ int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char
   mark(1);
   constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
   const int64_t waves = (dp.nblocks + BPW - 1) / BPW;
-  if (p.flags & TSENOR_FLAG_FP32_ITERATIONS) {
+  if (dp.T == 0) {
+    using L = DykstraLaunch<M, false>;
+    dykstra_sort_kernel<M, false, true><<<(unsigned)((waves + L::kWavesPerGroup - 1) / L::kWavesPerGroup),
+                                          L::kThreads, 0, stream>>>(dp, hdr, order, p.plan_out, p.tau_eff_out);
+  } else if (p.flags & TSENOR_FLAG_FP32_ITERATIONS) {
     using L = DykstraLaunch<M, true>;
     dykstra_sort_kernel<M, true><<<(unsigned)((waves + L::kWavesPerGroup - 1) / L::kWavesPerGroup), L::kThreads, 0,
                                    stream>>>(dp, hdr, order, p.plan_out, p.tau_eff_out);
