@@ -21,7 +21,8 @@
  *     the optional plan use leading dimension `cols`.
  *   - rows and cols must be multiples of M (the method never pads, Sec. 3.1);
  *     M must be one of 4, 8, 16, 32, 64 and 0 <= N <= M.  N == 0 and N == M are
- *     answered with the all-zero / all-one mask without iterating.
+ *     answered with the all-zero / all-one mask without iterating (objective_out
+ *     and prev_mask are TSENOR_ERR_UNSUPPORTED for them: there is nothing to compare).
  *   - The arithmetic of the Dykstra iterations, the sort keys and the swap scores
  *     is IEEE double precision on the device.
  */
@@ -100,7 +101,30 @@ typedef struct tsenor_problem {
   int64_t* stats_out;     /* device out, optional, 4 counters summed over blocks: [0] ones still missing after
                              greedy selection, [1] swaps applied with score <= 0, [2] blocks that needed more
                              than local_search_steps rounds, [3] ones still missing at return (STRICT_PAPER) */
+
+  /* ---- importance transform: the scores the layer-wise pruning frameworks of Sec. 4 hand to Eq. 1.
+   *      All of it is float arithmetic in this order: x = W + add_scale * add;  a = |x|;  a = a * col_scale[j];
+   *      importance = a (ABS) or a * a (SQUARE).  Zero-initialised fields give importance = |W| * col_scale. */
+  const void* add;        /* device, optional (NULL = none): matrix of W's dtype, shape and ld; with add_scale = 1/rho
+                             this is the ALPS score (W + V/rho)^2 of Proposition 1 */
+  float add_scale;        /* finite; ignored when add is NULL */
+  int32_t importance;     /* TSENOR_IMPORTANCE_ABS (0) or TSENOR_IMPORTANCE_SQUARE */
+
+  /* ---- further outputs, all optional (NULL = skip) ---- */
+  uint8_t* packed_out;    /* device out, rows x cols/8 bytes: bit (j & 7) of byte j >> 3 of row i is S_ij; needs
+                             cols % 8 == 0 */
+  void* pruned_out;       /* device out, rows x cols elements of W's dtype, leading dimension cols: x_ij where the
+                             mask keeps it, +0 elsewhere ("setting all elements outside the mask to zero", Sec. 4;
+                             the D-update of Proposition 1).  bf16 output rounds x to nearest-even */
+  double* objective_out;  /* device out, 2 doubles: [0] sum_ij S_ij * importance_ij of the returned mask (the
+                             objective of Eq. 1), [1] the same for prev_mask (0 if none).  Summed block by block in a
+                             fixed order: bitwise reproducible from run to run */
+  const uint8_t* prev_mask; /* device, optional, rows x cols bytes (0/1): the safeguard of App. A.1 (Assumption 1).
+                             If this mask scores strictly higher than the one just found, under the importance of
+                             THIS call, it is returned instead (mask, packed_out, pruned_out follow it) */
 } tsenor_problem;
+
+enum { TSENOR_IMPORTANCE_ABS = 0, TSENOR_IMPORTANCE_SQUARE = 1 };
 
 /* Bytes of device scratch that tsenor_mask_ex / tsenor_mask_batched need for these problems
  * (the sum over the batch).  0 on invalid arguments. */

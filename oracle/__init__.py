@@ -58,6 +58,10 @@ def _load():
         lib.tsenor_oracle_swap_scores.restype = i32
         lib.tsenor_oracle_mask.argtypes = [p, i64, i64, i64, p, i32, i32, dbl, i32, i32, i32, i32, i32, p, p, p, p]
         lib.tsenor_oracle_mask.restype = i32
+        lib.tsenor_oracle_importance_ex.argtypes = [p, p, ctypes.c_float, i64, i64, i64, p, i32, p, p]
+        lib.tsenor_oracle_importance_ex.restype = i32
+        lib.tsenor_oracle_objective.argtypes = [p, p, i64, i64, i32]
+        lib.tsenor_oracle_objective.restype = dbl
         lib.tsenor_oracle_num_threads.restype = i32
         lib.tsenor_oracle_set_threads.argtypes = [i32]
         _lib = lib
@@ -89,6 +93,54 @@ def importance(W, col_scale=None) -> np.ndarray:
     if rc:
         raise ValueError(f"tsenor_oracle_importance failed: {rc}")
     return out
+
+
+def importance_ex(W, *, add=None, add_scale: float = 0.0, col_scale=None, square: bool = False):
+    """Importance with the transforms of Sec. 4 / Proposition 1: x = W + add_scale*add, |x| * col_scale, optionally
+    squared, every step one float32 operation.  Returns (importance, x)."""
+    W = _f32(W)
+    a = None if add is None else _f32(add)
+    cs = None if col_scale is None else _f32(col_scale)
+    imp, val = np.empty_like(W), np.empty_like(W)
+    rc = _load().tsenor_oracle_importance_ex(_ptr(W), _ptr(a), float(add_scale), W.shape[0], W.shape[1], W.shape[1],
+                                             _ptr(cs), int(square), _ptr(imp), _ptr(val))
+    if rc:
+        raise ValueError(f"tsenor_oracle_importance_ex failed: {rc}")
+    return imp, val
+
+
+def objective(mask_, imp, M: int) -> float:
+    """Objective of Eq. (1): the importance the mask keeps, summed in double."""
+    mask_ = np.ascontiguousarray(mask_, dtype=np.uint8)
+    imp = _f32(imp)
+    return float(_load().tsenor_oracle_objective(_ptr(mask_), _ptr(imp), imp.shape[0], imp.shape[1], int(M)))
+
+
+def pack_bits(mask_) -> np.ndarray:
+    """Bit-packed mask: bit (j & 7) of byte j >> 3 of row i is S_ij."""
+    return np.packbits(np.ascontiguousarray(mask_, dtype=np.uint8), axis=1, bitorder="little")
+
+
+def solve_ex(W, N: int, M: int, tau: float, T: int, *, add=None, add_scale: float = 0.0, col_scale=None,
+             square: bool = False, tau_mode: int = TAU_ABSOLUTE, L: int = 10, strict_paper: bool = False,
+             cols_first: bool = False, prev_mask=None):
+    """The whole path with the importance transforms, the objective and the safeguard of App. A.1
+    (Assumption 1: if the previous mask keeps strictly more importance than the one found, it is returned).
+    Returns dict(mask, pruned, packed, objective, objective_prev, used_prev, stats, tau_eff, log_S)."""
+    imp, val = importance_ex(W, add=add, add_scale=add_scale, col_scale=col_scale, square=square)
+    te = tau_eff(imp, tau, tau_mode)
+    log_S = dykstra(imp, N, M, te, T, cols_first=cols_first)
+    m, stats = round_plan(log_S, imp, N, M, L=L, strict_paper=strict_paper)
+    obj = objective(m, imp, M)
+    obj_prev, used_prev = 0.0, False
+    if prev_mask is not None:
+        prev_mask = np.ascontiguousarray(prev_mask, dtype=np.uint8)
+        obj_prev = objective(prev_mask, imp, M)
+        if obj_prev > obj:
+            m, used_prev = prev_mask.copy(), True
+    return {"mask": m, "pruned": val * m, "packed": pack_bits(m), "objective": obj_prev if used_prev else obj,
+            "objective_new": obj, "objective_prev": obj_prev, "used_prev": used_prev, "stats": stats, "tau_eff": te,
+            "log_S": log_S}
 
 
 def tau_eff(imp, tau: float, tau_mode: int = TAU_ABSOLUTE) -> float:

@@ -329,3 +329,39 @@ int tsenor_oracle_mask(const float* W, int64_t rows, int64_t cols, int64_t ld, c
   if (!plan_log) free(ls);
   return rc;
 }
+
+/* Importance with the transforms of Sec. 4 / Proposition 1, every step one float operation in this order:
+ * x = W + add_scale * add;  a = |x|;  a = a * col_scale[j];  importance = a or a * a.
+ * value (optional) receives x, the number a kept entry carries. */
+int tsenor_oracle_importance_ex(const float* W, const float* add, float add_scale, int64_t rows, int64_t cols,
+                                int64_t ld, const float* col_scale, int square, float* imp, float* value) {
+  if (!W || !imp || rows <= 0 || cols <= 0 || ld < cols) return -1;
+  for (int64_t i = 0; i < rows; ++i)
+    for (int64_t j = 0; j < cols; ++j) {
+      float x = W[i * ld + j];
+      if (add) {
+        volatile float t = add_scale * add[i * ld + j]; /* rounded product, then rounded sum: no fused multiply-add */
+        x = x + t;
+      }
+      if (value) value[i * cols + j] = x;
+      volatile float a = fabsf(x);
+      if (col_scale) a = a * col_scale[j];
+      if (square) a = a * a;
+      imp[i * cols + j] = a;
+    }
+  return 0;
+}
+
+/* Objective of Eq. (1): sum of the importance the mask keeps, accumulated in double block by block. */
+double tsenor_oracle_objective(const uint8_t* mask, const float* imp, int64_t rows, int64_t cols, int M) {
+  double total = 0.0;
+  for (int64_t r0 = 0; r0 < rows; r0 += M)
+    for (int64_t c0 = 0; c0 < cols; c0 += M) {
+      double blk = 0.0;
+      for (int i = 0; i < M; ++i)
+        for (int j = 0; j < M; ++j)
+          if (mask[(r0 + i) * cols + c0 + j]) blk += (double)imp[(r0 + i) * cols + c0 + j];
+      total += blk;
+    }
+  return total;
+}

@@ -32,6 +32,8 @@ TSENOR_TAU_REL_MATRIX_MAX = 1
 TSENOR_FLAG_STRICT_PAPER = 1 << 0
 TSENOR_FLAG_COLS_FIRST = 1 << 1
 TSENOR_FLAG_FP32_ITERATIONS = 1 << 2
+TSENOR_IMPORTANCE_ABS = 0
+TSENOR_IMPORTANCE_SQUARE = 1
 
 EXPORTS = (
     "tsenor_workspace_bytes", "tsenor_mask_ex", "tsenor_mask_batched", "tsenor_mask", "tsenor_mask_ex_profile",
@@ -58,6 +60,13 @@ class tsenor_problem(ctypes.Structure):
         ("plan_out", ctypes.c_void_p),
         ("tau_eff_out", ctypes.c_void_p),
         ("stats_out", ctypes.c_void_p),
+        ("add", ctypes.c_void_p),
+        ("add_scale", ctypes.c_float),
+        ("importance", ctypes.c_int32),
+        ("packed_out", ctypes.c_void_p),
+        ("pruned_out", ctypes.c_void_p),
+        ("objective_out", ctypes.c_void_p),
+        ("prev_mask", ctypes.c_void_p),
     ]
 
 
@@ -123,7 +132,9 @@ def _dtype_code(W) -> int:
 
 
 def make_problem(W, N, M, tau, iters, *, mask, col_scale=None, tau_mode=TSENOR_TAU_ABSOLUTE,
-                 local_search_steps=10, flags=0, plan_out=None, tau_eff_out=None, stats_out=None) -> tsenor_problem:
+                 local_search_steps=10, flags=0, plan_out=None, tau_eff_out=None, stats_out=None, add=None,
+                 add_scale=0.0, importance=TSENOR_IMPORTANCE_ABS, packed_out=None, pruned_out=None,
+                 objective_out=None, prev_mask=None) -> tsenor_problem:
     """Fill a tsenor_problem from device tensors (no copies; the tensors must outlive the call)."""
     if W.dim() != 2 or W.stride(1) != 1:
         raise ValueError("W must be a 2-D tensor with unit column stride")
@@ -142,6 +153,16 @@ def make_problem(W, N, M, tau, iters, *, mask, col_scale=None, tau_mode=TSENOR_T
     p.plan_out = None if plan_out is None else plan_out.data_ptr()
     p.tau_eff_out = None if tau_eff_out is None else tau_eff_out.data_ptr()
     p.stats_out = None if stats_out is None else stats_out.data_ptr()
+    if add is not None:
+        if add.dtype != W.dtype or add.shape != W.shape or add.stride() != W.stride():
+            raise ValueError("add must have W's dtype, shape and strides")
+        p.add = add.data_ptr()
+        p.add_scale = float(add_scale)
+    p.importance = int(importance)
+    p.packed_out = None if packed_out is None else packed_out.data_ptr()
+    p.pruned_out = None if pruned_out is None else pruned_out.data_ptr()
+    p.objective_out = None if objective_out is None else objective_out.data_ptr()
+    p.prev_mask = None if prev_mask is None else prev_mask.data_ptr()
     return p
 
 
@@ -197,7 +218,9 @@ def tsenor_mask(W, N, M, tau, iters, mask=None, stream=None):
 
 
 def solve(W, N, M, tau, iters, *, col_scale=None, tau_mode=TSENOR_TAU_ABSOLUTE, local_search_steps=10, flags=0,
-          want_plan=False, want_stats=False, workspace=None, stream=None):
+          want_plan=False, want_stats=False, workspace=None, stream=None, add=None, add_scale=0.0,
+          importance=TSENOR_IMPORTANCE_ABS, want_packed=False, want_pruned=False, want_objective=False,
+          prev_mask=None):
     """Allocate outputs and scratch with torch, call tsenor_mask_ex once, return dict(mask[, plan, stats, tau_eff])."""
     import torch
 
@@ -206,9 +229,13 @@ def solve(W, N, M, tau, iters, *, col_scale=None, tau_mode=TSENOR_TAU_ABSOLUTE, 
     plan = torch.empty(W.shape, dtype=torch.float64, device=dev) if want_plan else None
     stats = torch.zeros(4, dtype=torch.int64, device=dev) if want_stats else None
     tau_eff = torch.zeros(1, dtype=torch.float64, device=dev)
+    packed = torch.empty((W.shape[0], W.shape[1] // 8), dtype=torch.uint8, device=dev) if want_packed else None
+    pruned = torch.empty(W.shape, dtype=W.dtype, device=dev) if want_pruned else None
+    objective = torch.zeros(2, dtype=torch.float64, device=dev) if want_objective else None
     p = make_problem(W, N, M, tau, iters, mask=mask, col_scale=col_scale, tau_mode=tau_mode,
                      local_search_steps=local_search_steps, flags=flags, plan_out=plan, tau_eff_out=tau_eff,
-                     stats_out=stats)
+                     stats_out=stats, add=add, add_scale=add_scale, importance=importance, packed_out=packed,
+                     pruned_out=pruned, objective_out=objective, prev_mask=prev_mask)
     need = tsenor_workspace_bytes([p])
     if need == 0:
         # invalid arguments: let the entry point name the reason
@@ -221,4 +248,10 @@ def solve(W, N, M, tau, iters, *, col_scale=None, tau_mode=TSENOR_TAU_ABSOLUTE, 
         out["plan"] = plan
     if want_stats:
         out["stats"] = stats
+    if want_packed:
+        out["packed"] = packed
+    if want_pruned:
+        out["pruned"] = pruned
+    if want_objective:
+        out["objective"] = objective
     return out

@@ -15,6 +15,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 instructions are kept out of every kernel
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # no implicit fused multiply-add: every rounding is the one written in the source (the kernels ask for
+    # fma() where they want it), so a host evaluation of the importance gives the same bits
+    "-ffp-contract=off",
     f"-I{ROOT / 'include'}",
 ]
 

@@ -9,33 +9,48 @@ namespace tsenor_dev {
 
 struct WsHeader {
   unsigned int max_bits;  // bit pattern of the largest importance seen (non-negative floats order as uints)
-  unsigned int pad;
+  unsigned int use_prev;  // safeguard verdict: 1 = the caller's previous mask scores higher and is returned
   double tau_eff;
   unsigned long long stats[4];
+  double objective[2];    // sum S*importance of the mask found / of the previous mask
 };
 static_assert(sizeof(WsHeader) <= 256, "header must fit its slot");
 
 struct DevProblem {
   const void* W;
+  const void* add;
   const float* col_scale;
   int64_t ld, cols, nblocks, bc;  // bc: blocks per block-row
   int dtype, N, T, transpose;
   int L, strict;
   double tau;
   int tau_mode;
+  float add_scale;
+  int square;
 };
 
-// importance of one weight: |w| or |w| * col_scale[j] as one float multiply (Sec. 4, Wanda-style scores)
-__device__ __forceinline__ float load_importance(const DevProblem& p, int64_t r, int64_t c) {
-  float w;
-  if (p.dtype == TSENOR_BF16) {
-    unsigned int b = reinterpret_cast<const unsigned short*>(p.W)[r * p.ld + c];
-    w = __uint_as_float(b << 16);
-  } else {
-    w = reinterpret_cast<const float*>(p.W)[r * p.ld + c];
+__device__ __forceinline__ float load_element(const void* base, int dtype, int64_t index) {
+  if (dtype == TSENOR_BF16) {
+    const unsigned int b = reinterpret_cast<const unsigned short*>(base)[index];
+    return __uint_as_float(b << 16);
   }
-  float a = fabsf(w);
-  if (p.col_scale) a = a * p.col_scale[c];
+  return reinterpret_cast<const float*>(base)[index];
+}
+
+// x = W + add_scale * add: the value a kept entry carries (Sec. 4; the ALPS D-update of Proposition 1).
+// Explicitly rounded operations: no fused multiply-add, so that a host evaluation gives the same bits.
+__device__ __forceinline__ float load_value(const DevProblem& p, int64_t r, int64_t c) {
+  const float w = load_element(p.W, p.dtype, r * p.ld + c);
+  if (!p.add) return w;
+  return __fadd_rn(w, __fmul_rn(p.add_scale, load_element(p.add, p.dtype, r * p.ld + c)));
+}
+
+// importance of one weight: |x| (times col_scale[j]) (squared), every step one float operation
+// (Sec. 4: Wanda-style scores; Proposition 1: (W + V/rho)^2)
+__device__ __forceinline__ float load_importance(const DevProblem& p, int64_t r, int64_t c) {
+  float a = fabsf(load_value(p, r, c));
+  if (p.col_scale) a = __fmul_rn(a, p.col_scale[c]);
+  if (p.square) a = __fmul_rn(a, a);
   return a;
 }
 

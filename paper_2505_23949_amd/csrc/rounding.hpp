@@ -109,11 +109,89 @@ __device__ __forceinline__ SwapBest group_best(SwapBest v) {
   }
 }
 
+template <int M, int STEP = 1>
+__device__ __forceinline__ double group_sum(double v) {
+  if constexpr (STEP < M) {
+    v += lane_xor<STEP>(v);
+    return group_sum<M, STEP * 2>(v);
+  } else {
+    return v;
+  }
+}
+
+// Sum of the per-block objectives in a fixed order (thread t adds blocks t, t+1024, ...; then a tree), and
+// the safeguard verdict of App. A.1 (Assumption 1): keep the previous mask if it scores strictly higher.
+__global__ __launch_bounds__(1024) void objective_kernel(const double* block_objective, int64_t nblocks, int have_prev,
+                                                         WsHeader* hdr, double* objective_out) {
+  __shared__ double part[2][1024];
+  double a = 0.0, b = 0.0;
+  for (int64_t k = threadIdx.x; k < nblocks; k += 1024) {
+    a += block_objective[2 * k];
+    b += block_objective[2 * k + 1];
+  }
+  part[0][threadIdx.x] = a;
+  part[1][threadIdx.x] = b;
+  __syncthreads();
+  for (int s = 512; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) {
+      part[0][threadIdx.x] += part[0][threadIdx.x + s];
+      part[1][threadIdx.x] += part[1][threadIdx.x + s];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const bool use_prev = have_prev && part[1][0] > part[0][0];
+    hdr->objective[0] = part[0][0];
+    hdr->objective[1] = part[1][0];
+    hdr->use_prev = use_prev ? 1u : 0u;
+    if (objective_out) {
+      objective_out[0] = use_prev ? part[1][0] : part[0][0];
+      objective_out[1] = have_prev ? part[1][0] : 0.0;
+    }
+  }
+}
+
+// Outputs derived from the final mask, 8 consecutive weights of a row per thread: the previous mask copied
+// over the new one if the safeguard says so, the bit-packed mask, and the pruned values x * S.
+__global__ __launch_bounds__(256) void emit_kernel(DevProblem p, int64_t rows, const WsHeader* hdr, uint8_t* mask,
+                                                   const uint8_t* prev_mask, uint8_t* packed_out, void* pruned_out) {
+  const bool use_prev = prev_mask && hdr->use_prev;
+  const int64_t per_row = p.cols / 8;
+  for (int64_t r = blockIdx.y; r < rows; r += gridDim.y)
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < per_row; v += (int64_t)gridDim.x * blockDim.x) {
+      const int64_t c = v * 8;
+      unsigned int bits = 0;
+      for (int k = 0; k < 8; ++k) {
+        uint8_t s = mask[r * p.cols + c + k];
+        if (use_prev) {
+          s = prev_mask[r * p.cols + c + k];
+          mask[r * p.cols + c + k] = s;
+        }
+        bits |= (unsigned int)(s & 1) << k;
+      }
+      if (packed_out) packed_out[r * per_row + v] = (uint8_t)bits;
+      if (pruned_out) {
+        for (int k = 0; k < 8; ++k) {
+          const float x = ((bits >> k) & 1) ? load_value(p, r, c + k) : 0.0f;
+          if (p.dtype == TSENOR_BF16) {
+            // round to nearest even; x is finite
+            const unsigned int u = __float_as_uint(x);
+            reinterpret_cast<unsigned short*>(pruned_out)[r * p.cols + c + k] =
+                (unsigned short)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+          } else {
+            reinterpret_cast<float*>(pruned_out)[r * p.cols + c + k] = x;
+          }
+        }
+      }
+    }
+}
+
 // Algorithm 2 lines 7-13 and the mask write.  M lanes per block (lane r owns row r and column r of the
 // block as bit masks), 64/M blocks per wave, one wave per workgroup.
 template <int M>
 __global__ __launch_bounds__(kWave) void finalize_kernel(DevProblem p, const block_mask_t<M>* rowmask, uint8_t* mask,
-                                                         WsHeader* hdr, int wide_store) {
+                                                         WsHeader* hdr, int wide_store, double* block_objective,
+                                                         const uint8_t* prev_mask) {
   using mask_t = block_mask_t<M>;
   constexpr int MM = M * M, G = kWave / M;
   __shared__ float imp[G][MM];
@@ -135,7 +213,7 @@ __global__ __launch_bounds__(kWave) void finalize_kernel(DevProblem p, const blo
   const auto popc = [](mask_t v) { return mask_popc(v); };
   const unsigned long long gmask = (M == 64 ? ~0ull : ((1ull << M) - 1)) << (g * M);
   const bool any_short = __any(popc(rowm[g][ql]) < p.N);
-  if (any_short) {
+  if (any_short || block_objective) {
     // local search scores on the importance (Eq. 5), staged in LDS: row k of every block per step
     for (int k = 0; k < M; ++k) imp[g][k * M + ql] = load_importance(p, r0 + k, c0 + ql);
   }
@@ -205,6 +283,23 @@ __global__ __launch_bounds__(kWave) void finalize_kernel(DevProblem p, const blo
       }
     } else {
       for (int k = 0; k < M; ++k) dst[k] = (uint8_t)((bits >> k) & 1);
+    }
+    if (block_objective) {
+      // sum S * importance of this block for the mask found and for the caller's previous mask: every lane
+      // sums its row left to right, the rows are then added in a fixed butterfly order
+      double mine = 0.0, theirs = 0.0;
+      const uint8_t* prev = prev_mask ? prev_mask + (r0 + ql) * p.cols + c0 : nullptr;
+      for (int k = 0; k < M; ++k) {
+        const double v = (double)imp[g][ql * M + k];
+        if ((bits >> k) & 1) mine += v;
+        if (prev && prev[k]) theirs += v;
+      }
+      mine = group_sum<M>(mine);
+      theirs = group_sum<M>(theirs);
+      if (ql == 0) {
+        block_objective[2 * blk] = mine;
+        block_objective[2 * blk + 1] = theirs;
+      }
     }
     const int left = p.N - popc(bits);
     if (left) atomicAdd(&hdr->stats[3], (unsigned long long)left);

@@ -24,7 +24,8 @@ using namespace tsenor_dev;
 
 __global__ void init_kernel(WsHeader* hdr) {
   hdr->max_bits = 0u;
-  hdr->pad = 0u;
+  hdr->use_prev = 0u;
+  hdr->objective[0] = hdr->objective[1] = 0.0;
   hdr->tau_eff = 0.0;
   for (int k = 0; k < 4; ++k) hdr->stats[k] = 0ull;
 }
@@ -98,7 +99,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-  size_t header, order, accept, total;
+  size_t header, order, accept, objective, total;
 };
 
 // greedy's output: M row bit masks per block, 32-bit words up to M = 32, 64-bit for M = 64
@@ -111,7 +112,8 @@ WsLayout layout_of(const tsenor_problem& p) {
   l.header = 0;
   l.order = kAlign;
   l.accept = l.order + align_up(elems * sizeof(unsigned short));
-  l.total = l.accept + align_up(nblocks * rowmask_bytes_per_block(p.M));
+  l.objective = l.accept + align_up(nblocks * rowmask_bytes_per_block(p.M));
+  l.total = l.objective + align_up(nblocks * 2 * sizeof(double));  // per-block objectives (new, previous mask)
   return l;
 }
 
@@ -127,6 +129,10 @@ int validate(const tsenor_problem* p) {
   if (p->N < 0 || p->N > p->M) return TSENOR_ERR_NM;
   if (!(p->tau > 0.0) || !std::isfinite(p->tau) || p->iters < 0 || p->local_search_steps < 0) return TSENOR_ERR_PARAM;
   if (p->tau_mode == TSENOR_TAU_REL_MATRIX_MAX && p->tau < 1.0 / 690.0) return TSENOR_ERR_PARAM;
+  if (p->importance != TSENOR_IMPORTANCE_ABS && p->importance != TSENOR_IMPORTANCE_SQUARE) return TSENOR_ERR_UNSUPPORTED;
+  if (p->add && !std::isfinite(p->add_scale)) return TSENOR_ERR_PARAM;
+  if ((p->packed_out || p->pruned_out || p->prev_mask) && p->cols % 8) return TSENOR_ERR_SHAPE;
+  if ((p->N == 0 || p->N == p->M) && (p->objective_out || p->prev_mask)) return TSENOR_ERR_UNSUPPORTED;
   return TSENOR_OK;
 }
 
@@ -145,7 +151,7 @@ int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char
   if (dp.tau_mode == TSENOR_TAU_REL_MATRIX_MAX) {
     const size_t esize = dp.dtype == TSENOR_BF16 ? 2 : 4;
     const bool vec = dp.cols % 8 == 0 && reinterpret_cast<uintptr_t>(dp.W) % 16 == 0 && (dp.ld * esize) % 16 == 0 &&
-                     reinterpret_cast<uintptr_t>(dp.col_scale) % 16 == 0;
+                     reinterpret_cast<uintptr_t>(dp.col_scale) % 16 == 0 && !dp.add && !dp.square;
     const int64_t per_row = vec ? dp.cols / 8 : dp.cols;
     const unsigned gx = (unsigned)std::min<int64_t>((per_row + 255) / 256, 16);
     const dim3 grid(gx, (unsigned)std::min<int64_t>(rows, std::max<unsigned>(1024 / gx, 1)));  // ~1024 workgroups
@@ -176,7 +182,18 @@ int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char
   mark(3);
   constexpr int G = kWave / M;
   const int wide = reinterpret_cast<uintptr_t>(p.mask) % 16 == 0;
-  finalize_kernel<M><<<(unsigned)((dp.nblocks + G - 1) / G), kWave, 0, stream>>>(dp, accept, p.mask, hdr, wide);
+  const bool want_objective = p.objective_out || p.prev_mask;
+  double* block_objective = want_objective ? reinterpret_cast<double*>(ws + l.objective) : nullptr;
+  finalize_kernel<M><<<(unsigned)((dp.nblocks + G - 1) / G), kWave, 0, stream>>>(dp, accept, p.mask, hdr, wide,
+                                                                                  block_objective, p.prev_mask);
+  if (want_objective)
+    objective_kernel<<<1, 1024, 0, stream>>>(block_objective, dp.nblocks, p.prev_mask != nullptr, hdr, p.objective_out);
+  if (p.packed_out || p.pruned_out || p.prev_mask) {
+    const int64_t per_row = dp.cols / 8;
+    const unsigned gx = (unsigned)std::min<int64_t>((per_row + 255) / 256, 16);
+    const dim3 grid(gx, (unsigned)std::min<int64_t>(rows, std::max<unsigned>(2048 / gx, 1)));
+    emit_kernel<<<grid, 256, 0, stream>>>(dp, rows, hdr, p.mask, p.prev_mask, p.packed_out, p.pruned_out);
+  }
   if (p.stats_out) stats_kernel<<<1, 1, 0, stream>>>(hdr, p.stats_out);
   mark(4);
   return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
@@ -189,17 +206,31 @@ int run_one(const tsenor_problem& p, char* ws, hipStream_t stream, hipEvent_t* e
     if (ev)
       for (int k = 0; k < 4; ++k) (void)hipEventRecord(ev[k], stream);
     fill_kernel<<<grid, 256, 0, stream>>>(p.mask, total, p.N == 0 ? 0 : 1);
-    // the plan of a degenerate problem is the mask itself; stats are zero
-    if (p.stats_out || p.tau_eff_out || p.plan_out) {
-      WsHeader* hdr = reinterpret_cast<WsHeader*>(ws);
-      init_kernel<<<1, 1, 0, stream>>>(hdr);
-      if (p.stats_out) stats_kernel<<<1, 1, 0, stream>>>(hdr, p.stats_out);
+    // the mask of a degenerate problem needs no solve; stats are zero
+    WsHeader* hdr = reinterpret_cast<WsHeader*>(ws);
+    init_kernel<<<1, 1, 0, stream>>>(hdr);
+    if (p.stats_out) stats_kernel<<<1, 1, 0, stream>>>(hdr, p.stats_out);
+    if (p.packed_out || p.pruned_out) {
+      DevProblem dq = {};
+      dq.W = p.W;
+      dq.add = p.add;
+      dq.add_scale = p.add ? p.add_scale : 0.0f;
+      dq.ld = p.ld;
+      dq.cols = p.cols;
+      dq.dtype = p.dtype;
+      const int64_t per_row = p.cols / 8;
+      const unsigned gx = (unsigned)std::min<int64_t>((per_row + 255) / 256, 16);
+      const dim3 egrid(gx, (unsigned)std::min<int64_t>(p.rows, std::max<unsigned>(2048 / gx, 1)));
+      emit_kernel<<<egrid, 256, 0, stream>>>(dq, p.rows, hdr, p.mask, nullptr, p.packed_out, p.pruned_out);
     }
     if (ev) (void)hipEventRecord(ev[4], stream);
     return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
   }
   DevProblem dp;
   dp.W = p.W;
+  dp.add = p.add;
+  dp.add_scale = p.add ? p.add_scale : 0.0f;
+  dp.square = p.importance == TSENOR_IMPORTANCE_SQUARE;
   dp.col_scale = p.col_scale;
   dp.ld = p.ld;
   dp.cols = p.cols;

@@ -109,8 +109,9 @@ def test_workspace_bytes(lib):
         need = lib.tsenor_workspace_bytes(ctypes.byref(p), 1)
         blocks = rows * cols // (M * M)
         # header + one uint16 per weight (greedy scan order) + M row bit masks per block (32- or 64-bit words)
-        lower = 256 + 2 * rows * cols + blocks * M * (8 if M > 32 else 4)
-        assert lower <= need <= lower + 512
+        # + two doubles per block (objective of the mask found and of the caller's previous mask)
+        lower = 256 + 2 * rows * cols + blocks * M * (8 if M > 32 else 4) + 16 * blocks
+        assert lower <= need <= lower + 768
     arr = (b.tsenor_problem * 2)(_problem(), _problem(M=32, N=16, rows=64, cols=64, ld=64))
     assert lib.tsenor_workspace_bytes(arr, 2) == sum(lib.tsenor_workspace_bytes(ctypes.byref(x), 1) for x in arr)
     assert lib.tsenor_workspace_bytes(ctypes.byref(_problem(M=5)), 1) == 0
@@ -162,3 +163,20 @@ def test_bf16_round_trip_of_the_input_generator():
     assert g["W_store"].dtype == np.uint16 and np.array_equal(synth.bf16_bits_to_f32(g["W_store"]), g["W_f32"])
     g2 = synth.generate(synth.CONFIGS["cfg3_16of32_4096x14336"].scaled(64, 64))
     assert np.array_equal(g["W_store"], g2["W_store"]) and np.array_equal(g["col_scale"], g2["col_scale"])
+
+
+def test_validation_of_the_extended_fields(lib):
+    from paper_2505_23949_amd import binding as b
+
+    def call(p):
+        return lib.tsenor_mask_ex(ctypes.byref(p), ctypes.c_void_p(0), 0, None)   # stops at the workspace check
+
+    assert call(_problem(importance=2)) == b.TSENOR_ERR_UNSUPPORTED
+    assert call(_problem(add=0x3000, add_scale=float("inf"))) == b.TSENOR_ERR_PARAM
+    assert call(_problem(add=0x3000, add_scale=0.5)) == b.TSENOR_ERR_WORKSPACE
+    odd = dict(M=4, N=2, rows=8, cols=12, ld=12)
+    assert call(_problem(**odd)) == b.TSENOR_ERR_WORKSPACE
+    for field in ("packed_out", "pruned_out", "prev_mask"):
+        assert call(_problem(**odd, **{field: 0x4000})) == b.TSENOR_ERR_SHAPE
+    assert call(_problem(N=16, objective_out=0x4000)) == b.TSENOR_ERR_UNSUPPORTED
+    assert call(_problem(N=0, prev_mask=0x4000)) == b.TSENOR_ERR_UNSUPPORTED

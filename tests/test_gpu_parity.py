@@ -434,3 +434,111 @@ def test_hip_graph_capture_and_replay(dev):
         assert torch.equal(mask, eager_mask), f"replay {replay}"
         assert torch.equal(stats, eager_stats), f"replay {replay}"
         assert torch.isfinite(scratch)
+
+
+# ----------------------------------------------------------------------------------------------------
+# Importance transforms (Sec. 4, Proposition 1), objective, bit-packed mask, pruned weights, safeguard
+# ----------------------------------------------------------------------------------------------------
+
+def _bf16_to_f32_np(t):
+    return synth.bf16_bits_to_f32(t.view(__import__("torch").int16).cpu().numpy().view(np.uint16))
+
+
+@pytest.mark.parametrize("dtype,N,M,square", [("f32", 8, 16, True), ("bf16", 16, 32, True), ("f32", 2, 4, False),
+                                              ("f32", 32, 64, True)])
+def test_alps_style_importance_and_outputs(dev, dtype, N, M, square):
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    rng = np.random.Generator(np.random.Philox(700 + M))
+    rows, cols = 4 * M, 8 * M
+    W = (0.02 * rng.standard_normal((rows, cols))).astype(np.float32)
+    V = (0.01 * rng.standard_normal((rows, cols))).astype(np.float32)
+    c = rng.lognormal(0.0, 0.5, cols).astype(np.float32)
+    if dtype == "bf16":
+        Wb, Vb = synth.f32_to_bf16_bits(W), synth.f32_to_bf16_bits(V)
+        W, V = synth.bf16_bits_to_f32(Wb), synth.bf16_bits_to_f32(Vb)
+        Wd = torch.from_numpy(Wb.view(np.int16)).to(dev).view(torch.bfloat16)
+        Vd = torch.from_numpy(Vb.view(np.int16)).to(dev).view(torch.bfloat16)
+    else:
+        Wd, Vd = torch.from_numpy(W).to(dev), torch.from_numpy(V).to(dev)
+    cd = torch.from_numpy(c).to(dev)
+    rho = 3.0
+    add_scale = float(np.float32(1.0 / rho))
+    imode = binding.TSENOR_IMPORTANCE_SQUARE if square else binding.TSENOR_IMPORTANCE_ABS
+    print(f"[case] transforms {dtype} {N}:{M} square={square}", flush=True)
+    res = binding.solve(Wd, N, M, 0.01, 120, col_scale=cd, tau_mode=binding.TSENOR_TAU_REL_MATRIX_MAX, add=Vd,
+                        add_scale=add_scale, importance=imode, want_plan=True, want_stats=True, want_packed=True,
+                        want_pruned=True, want_objective=True)
+    torch.cuda.synchronize()
+    ref = oracle.solve_ex(W, N, M, 0.01, 120, add=V, add_scale=add_scale, col_scale=c, square=square,
+                          tau_mode=oracle.TAU_REL_MATRIX_MAX)
+    assert float(res["tau_eff"].cpu()[0]) == ref["tau_eff"]
+    assert np.abs(res["plan"].cpu().numpy() - np.exp(ref["log_S"])).max() <= PLAN_ATOL
+    mask = res["mask"].cpu().numpy()
+    assert np.array_equal(mask, ref["mask"])
+    assert np.array_equal(res["stats"].cpu().numpy(), ref["stats"])
+    assert np.array_equal(res["packed"].cpu().numpy(), ref["packed"])
+    obj = res["objective"].cpu().numpy()
+    assert abs(obj[0] - ref["objective"]) <= 1e-12 * ref["objective"] and obj[1] == 0.0
+    if dtype == "bf16":
+        pruned = _bf16_to_f32_np(res["pruned"])
+        want = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(ref["pruned"]))      # x rounded to bf16, nearest even
+    else:
+        pruned, want = res["pruned"].cpu().numpy(), ref["pruned"]
+    assert np.array_equal(pruned, want)
+    assert np.all(pruned[mask == 0] == 0) and not np.signbit(pruned[mask == 0]).any()
+
+
+def test_safeguard_keeps_the_better_previous_mask(dev):
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.CONFIGS["cfg2_8of16_4096"].scaled(64, 128)
+    g = synth.generate(w)
+    W, _ = _to_device(g, w, dev)
+    imp = oracle.importance(g["W_f32"])
+    good = oracle.mask(g["W_f32"], w.N, w.M, w.tau, w.iters, tau_mode=w.tau_mode)["mask"]
+    bad, _ = oracle.round_plan(-imp.astype(np.float64), imp, w.N, w.M)           # keeps the smallest weights
+    for prev, greedy_only in [(bad, False), (good, True)]:
+        prev_d = torch.from_numpy(prev).to(dev)
+        kw = dict(tau_mode=w.tau_mode, prev_mask=prev_d, want_objective=True, want_packed=True, want_pruned=True)
+        if greedy_only:   # a weak new solution: greedy on the importance itself, no local search
+            res = binding.solve(W, w.N, w.M, w.tau, 0, local_search_steps=0, flags=binding.TSENOR_FLAG_STRICT_PAPER, **kw)
+            ref = oracle.solve_ex(g["W_f32"], w.N, w.M, w.tau, 0, tau_mode=w.tau_mode, L=0, strict_paper=True,
+                                  prev_mask=prev)
+        else:
+            res = binding.solve(W, w.N, w.M, w.tau, w.iters, **kw)
+            ref = oracle.solve_ex(g["W_f32"], w.N, w.M, w.tau, w.iters, tau_mode=w.tau_mode, prev_mask=prev)
+        torch.cuda.synchronize()
+        assert ref["used_prev"] == greedy_only
+        obj = res["objective"].cpu().numpy()
+        assert np.array_equal(res["mask"].cpu().numpy(), ref["mask"])
+        assert np.array_equal(res["packed"].cpu().numpy(), ref["packed"])
+        assert np.array_equal(res["pruned"].cpu().numpy(), ref["pruned"])
+        assert abs(obj[0] - ref["objective"]) <= 1e-12 * ref["objective"]
+        assert abs(obj[1] - ref["objective_prev"]) <= 1e-12 * ref["objective_prev"]
+
+
+def test_objective_is_reproducible_and_degenerate_outputs(dev):
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.CONFIGS["cfg3_16of32_4096x14336"].scaled(256, 512)
+    g = synth.generate(w)
+    W, cs = _to_device(g, w, dev)
+    objs = [binding.solve(W, w.N, w.M, w.tau, 30, col_scale=cs, tau_mode=w.tau_mode, want_objective=True)["objective"]
+            .cpu().numpy()[0] for _ in range(3)]
+    assert objs[0] == objs[1] == objs[2]                     # fixed summation order: bitwise equal
+    Wf = torch.from_numpy(g["W_f32"]).to(dev)
+    full = binding.solve(Wf, 32, 32, 0.01, 5, want_packed=True, want_pruned=True)
+    none = binding.solve(Wf, 0, 32, 0.01, 5, want_packed=True, want_pruned=True)
+    torch.cuda.synchronize()
+    assert torch.equal(full["pruned"], Wf) and bool((full["packed"] == 255).all())
+    assert not none["pruned"].any() and not none["packed"].any()
+    with pytest.raises(binding.TsenorError) as e:
+        binding.solve(Wf, 32, 32, 0.01, 5, want_objective=True)
+    assert e.value.status == binding.TSENOR_ERR_UNSUPPORTED

@@ -408,3 +408,49 @@ def test_log_domain_survives_large_logits():
     assert np.isfinite(res["log_S"]).all() and S.max() <= 1.0
     assert np.abs(S.sum(axis=0) - 16).max() < 0.5 and np.abs(S.sum(axis=1) - 16).max() < 0.5
     assert exact.is_transposable_nm(res["mask"], 16, 32)
+
+
+# ----------------------------------------------------------------------------------------------
+# Importance transforms of Sec. 4 / Proposition 1, objective of Eq. (1), safeguard of App. A.1
+# ----------------------------------------------------------------------------------------------
+
+def test_importance_transforms_are_single_float_operations():
+    rng = np.random.default_rng(31)
+    W = rng.standard_normal((8, 16)).astype(np.float32)
+    V = rng.standard_normal((8, 16)).astype(np.float32)
+    c = rng.lognormal(0, 1, 16).astype(np.float32)
+    f32 = np.float32
+    x = (W + (f32(0.37) * V).astype(f32)).astype(f32)
+    imp, val = oracle.importance_ex(W, add=V, add_scale=0.37, col_scale=c, square=True)
+    a = (np.abs(x) * c).astype(f32)
+    assert np.array_equal(val, x) and np.array_equal(imp, (a * a).astype(f32))
+    imp2, val2 = oracle.importance_ex(W, col_scale=c)
+    assert np.array_equal(val2, W) and np.array_equal(imp2, oracle.importance(W, c))
+    # (W + V/rho)^2 of Proposition 1 with rho = 4
+    imp3, _ = oracle.importance_ex(W, add=V, add_scale=0.25, square=True)
+    assert np.allclose(imp3, (W.astype(np.float64) + V / 4.0) ** 2, rtol=1e-6)
+
+
+def test_objective_packing_and_safeguard():
+    rng = np.random.default_rng(32)
+    W = rng.standard_normal((16, 32)).astype(np.float32)
+    imp = oracle.importance(W)
+    res = oracle.solve_ex(W, 4, 8, 0.01, 100, tau_mode=oracle.TAU_REL_MATRIX_MAX)
+    m = res["mask"]
+    assert abs(res["objective"] - float((m * imp.astype(np.float64)).sum())) < 1e-9
+    assert np.array_equal(res["pruned"], W * m)
+    bits = np.unpackbits(res["packed"], axis=1, bitorder="little")
+    assert np.array_equal(bits, m) and res["packed"][0, 0] == sum(int(m[0, k]) << k for k in range(8))
+    # a previous mask that is worse is ignored, one that is better (the exact optimum) replaces the result
+    worse, _ = oracle.round_plan(-imp.astype(np.float64), imp, 4, 8)          # greedy on the smallest weights
+    r1 = oracle.solve_ex(W, 4, 8, 0.01, 100, tau_mode=oracle.TAU_REL_MATRIX_MAX, prev_mask=worse)
+    assert not r1["used_prev"] and np.array_equal(r1["mask"], m) and r1["objective_prev"] < r1["objective"]
+    best = np.zeros_like(m)
+    for b in range(8):
+        r0, c0 = (b // 4) * 8, (b % 4) * 8
+        best[r0:r0 + 8, c0:c0 + 8] = np.round(exact.lp_optimum(imp[r0:r0 + 8, c0:c0 + 8], 4)[1]).astype(np.uint8)
+    r2 = oracle.solve_ex(W, 4, 8, 0.01, 0, tau_mode=oracle.TAU_REL_MATRIX_MAX, L=0, strict_paper=True, prev_mask=best)
+    assert r2["objective_prev"] >= r2["objective_new"]
+    if r2["objective_prev"] > r2["objective_new"]:
+        assert r2["used_prev"] and np.array_equal(r2["mask"], best) and r2["objective"] == r2["objective_prev"]
+        assert np.array_equal(r2["pruned"], W * best)
