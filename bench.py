@@ -47,6 +47,51 @@ def recorded_traffic(workload: str, fp32: bool):
     return None
 
 
+def bench_layer(args) -> int:
+    """Secondary workload: the seven projection matrices of one 8B decoder layer (fp32, 16:32, Wanda-style
+    importance) through ONE tsenor_mask_batched call per step.  Wall-clock only (no per-kernel split)."""
+    import numpy as np
+    import torch
+
+    from paper_2505_23949_amd import binding, synth
+
+    dev = torch.device("cuda:0")
+    ws = synth.layer_workloads(0)
+    keep, probs = [], []
+    for w in ws:
+        g = synth.generate(w)
+        W = torch.from_numpy(g["W_store"]).to(dev)
+        cs = torch.from_numpy(g["col_scale"]).to(dev)
+        mask = torch.empty(W.shape, dtype=torch.uint8, device=dev)
+        flags = binding.TSENOR_FLAG_FP32_ITERATIONS if args.fp32_iterations else 0
+        probs.append(binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask, col_scale=cs, tau_mode=w.tau_mode,
+                                          flags=flags))
+        keep += [W, cs, mask]
+    work = torch.empty(binding.tsenor_workspace_bytes(probs), dtype=torch.uint8, device=dev)
+    for _ in range(args.warmup):
+        binding.tsenor_mask_batched(probs, work)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        binding.tsenor_mask_batched(probs, work)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    weights = sum(w.rows * w.cols for w in ws)
+    out = {
+        "metric": "masked weights/s (Dykstra+rounding), 16:32, one 8B decoder layer per batched call",
+        "value": round(weights / (ms_per_step * 1e-3), 1), "unit": "masked weights/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if args.fp32_iterations else "f64",
+        "data": "synthetic",
+        "config": {"workload": "cfg4_layer", "matrices": [[w.rows, w.cols] for w in ws], "weights": weights,
+                   "N": 16, "M": 32, "iters": 300, "tau": 0.005, "tau_mode": "rel_matrix_max", "storage": "f32",
+                   "importance": "wanda"},
+        "roofline": None, "cpu_baseline": None,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +119,8 @@ def main() -> int:
     from paper_2505_23949_amd import binding, synth
 
     binding.load()
+    if args.workload == "cfg4_layer":
+        return bench_layer(args)
     w = synth.CONFIGS[args.workload]
     if args.rows and args.cols:
         w = w.scaled(args.rows, args.cols)

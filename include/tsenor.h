@@ -135,8 +135,10 @@ size_t tsenor_workspace_bytes(const tsenor_problem* problems, int count);
  * are scratch.  Calls that overlap in time must not share a workspace. */
 int tsenor_mask_ex(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream);
 
-/* The same for `count` matrices (for example the seven projections of a decoder layer), enqueued
- * back to back on one stream; problems may differ in every field. */
+/* The same for `count` matrices (for example the seven projections of a decoder layer) on one stream.
+ * Problems may differ in every field.  Those that share M and the kernel variant (default, fp32 iterations,
+ * iters == 0) go through the kernels together, up to 16 matrices per launch: one launch of every kernel
+ * serves the whole group.  Results are those of `count` separate tsenor_mask_ex calls, bit for bit. */
 int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspace, size_t workspace_bytes,
                         tsenor_stream_t stream);
 

@@ -319,22 +319,28 @@ struct DykstraLaunch {
 // ZERO_T: the instantiation for T = 0 (no iterations, keys are K itself).  It is a template parameter
 // rather than a branch because keeping both paths in one kernel costs the iterating path ~40 registers.
 template <int M, bool FAST, bool ZERO_T = false>
-__global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), 2) void dykstra_sort_kernel(
-    DevProblem p, const WsHeader* hdr, unsigned short* order, double* plan_out, double* tau_eff_out) {
+__global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), 2) void dykstra_sort_kernel(Batch batch) {
   using T = Tiling<M>;
+  const int which = find_problem(batch, blockIdx.x);
+  const DevProblem p = batch.e[which].p;
+  const WsHeader* hdr = batch.e[which].hdr;
+  unsigned short* order = batch.e[which].order;
+  double* plan_out = batch.e[which].plan_out;
+  double* tau_eff_out = batch.e[which].tau_eff_out;
+  const unsigned int group = blockIdx.x - batch.first[which];  // workgroup index within the matrix
   constexpr int GX = 1 << T::NX, GY = 1 << T::NY, TH = M / GY, TW = M / GX, LPB = GX * GY, BPW = kWave / LPB,
                 E = TH * TW, SHX = ilog2(TH) - T::NX, WPG = DykstraLaunch<M, FAST>::kWavesPerGroup;
   static_assert(TH >= GX && TW >= GY, "every lane must end a reduce-scatter with at least one sum");
   __shared__ double kap_lds[FAST ? WPG : 1][FAST ? E : 1][FAST ? kWave : 1];
   const int lane = threadIdx.x & (kWave - 1), wave_in_group = threadIdx.x / kWave;
-  const int64_t wave = (int64_t)blockIdx.x * WPG + wave_in_group;
+  const int64_t wave = (int64_t)group * WPG + wave_in_group;
   const int q = lane % LPB, gx = q % GX, gy = q / GX;
   int64_t blk = wave * BPW + lane / LPB;
   const bool active = blk < p.nblocks;
   if (!active) blk = p.nblocks - 1;  // idle lanes shadow the last block and write nothing
   const int64_t r0 = (blk / p.bc) * M, c0 = (blk % p.bc) * M;
   const double tau_eff = tau_eff_of(p, hdr);
-  if (tau_eff_out && blockIdx.x == 0 && threadIdx.x == 0) *tau_eff_out = tau_eff;
+  if (tau_eff_out && group == 0 && threadIdx.x == 0) *tau_eff_out = tau_eff;
 
   // register (a, b) of this lane <-> in-kernel coordinates (ri, cj) of the block.  Each phase of the
   // kernel takes its own opaque copy of the lane offsets, so that element addresses are recomputed where

@@ -29,6 +29,43 @@ struct DevProblem {
   int square;
 };
 
+// One fused launch serves up to kMaxBatch matrices that share M and the kernel variant: every kernel gets the
+// table by value, finds the matrix its workgroup belongs to from the prefix `first`, and reads that entry.
+// A matrix owns whole workgroups, so the choice is uniform over a workgroup.
+constexpr int kMaxBatch = 16;
+
+struct BatchEntry {
+  DevProblem p;
+  int64_t rows;
+  WsHeader* hdr;                // workspace slices of this matrix
+  unsigned short* order;
+  void* rowmask;
+  double* block_objective;      // NULL: no objective asked for
+  uint8_t* mask;                // outputs of the caller (NULL where optional and not asked for)
+  double* plan_out;
+  double* tau_eff_out;
+  int64_t* stats_out;
+  uint8_t* packed_out;
+  void* pruned_out;
+  double* objective_out;
+  const uint8_t* prev_mask;
+  int wide_store;               // mask rows can be written with 16-byte stores
+  int absmax_vec;               // rows can be read with 16-byte loads by the maximum pre-pass
+};
+
+struct Batch {
+  int count;
+  unsigned int first[kMaxBatch + 1];  // first workgroup of every matrix in the launch at hand
+  BatchEntry e[kMaxBatch];
+};
+static_assert(sizeof(Batch) <= 4096, "the table travels as a kernel argument");
+
+__device__ __forceinline__ int find_problem(const Batch& b, unsigned int workgroup) {
+  int k = 0;
+  while (k + 1 < b.count && workgroup >= b.first[k + 1]) ++k;
+  return k;
+}
+
 __device__ __forceinline__ float load_element(const void* base, int dtype, int64_t index) {
   if (dtype == TSENOR_BF16) {
     const unsigned int b = reinterpret_cast<const unsigned short*>(base)[index];

@@ -25,14 +25,19 @@ __device__ __forceinline__ int mask_popc(mask_t v) {
 // every lane of the wave does useful work; the state of a lane (M row masks, M column counters) lives in
 // LDS.  Output: the mask as M row bit masks per block (bit c of word r = S[r][c]).
 template <int M>
-__global__ __launch_bounds__(kWave) void greedy_kernel(const unsigned short* order, int64_t nblocks, int N,
-                                                       block_mask_t<M>* rowmask, WsHeader* hdr) {
+__global__ __launch_bounds__(kWave) void greedy_kernel(Batch batch) {
   using mask_t = block_mask_t<M>;
   constexpr int MM = M * M;
   __shared__ mask_t rowbits[M][kWave];
   __shared__ unsigned char colcnt[M][kWave];
+  const int which = find_problem(batch, blockIdx.x);
+  const unsigned short* order = batch.e[which].order;
+  const int64_t nblocks = batch.e[which].p.nblocks;
+  const int N = batch.e[which].p.N;
+  mask_t* rowmask = static_cast<mask_t*>(batch.e[which].rowmask);
+  WsHeader* hdr = batch.e[which].hdr;
   const int lane = threadIdx.x;
-  const int64_t blk = (int64_t)blockIdx.x * kWave + lane;
+  const int64_t blk = (int64_t)(blockIdx.x - batch.first[which]) * kWave + lane;
   for (int k = 0; k < M; ++k) {
     rowbits[k][lane] = 0;
     colcnt[k][lane] = 0;
@@ -121,8 +126,14 @@ __device__ __forceinline__ double group_sum(double v) {
 
 // Sum of the per-block objectives in a fixed order (thread t adds blocks t, t+1024, ...; then a tree), and
 // the safeguard verdict of App. A.1 (Assumption 1): keep the previous mask if it scores strictly higher.
-__global__ __launch_bounds__(1024) void objective_kernel(const double* block_objective, int64_t nblocks, int have_prev,
-                                                         WsHeader* hdr, double* objective_out) {
+__global__ __launch_bounds__(1024) void objective_kernel(Batch batch) {
+  // one workgroup per matrix of the batch
+  const double* block_objective = batch.e[blockIdx.x].block_objective;
+  if (!block_objective) return;
+  const int64_t nblocks = batch.e[blockIdx.x].p.nblocks;
+  const bool have_prev = batch.e[blockIdx.x].prev_mask != nullptr;
+  WsHeader* hdr = batch.e[blockIdx.x].hdr;
+  double* objective_out = batch.e[blockIdx.x].objective_out;
   __shared__ double part[2][1024];
   double a = 0.0, b = 0.0;
   for (int64_t k = threadIdx.x; k < nblocks; k += 1024) {
@@ -153,9 +164,17 @@ __global__ __launch_bounds__(1024) void objective_kernel(const double* block_obj
 
 // Outputs derived from the final mask, 8 consecutive weights of a row per thread: the previous mask copied
 // over the new one if the safeguard says so, the bit-packed mask, and the pruned values x * S.
-__global__ __launch_bounds__(256) void emit_kernel(DevProblem p, int64_t rows, const WsHeader* hdr, uint8_t* mask,
-                                                   const uint8_t* prev_mask, uint8_t* packed_out, void* pruned_out) {
-  const bool use_prev = prev_mask && hdr->use_prev;
+__global__ __launch_bounds__(256) void emit_kernel(Batch batch) {
+  // blockIdx.z: matrix of the batch; x and y stride over its 8-weight vectors and rows
+  const BatchEntry& e = batch.e[blockIdx.z];
+  const uint8_t* prev_mask = e.prev_mask;
+  uint8_t* packed_out = e.packed_out;
+  void* pruned_out = e.pruned_out;
+  if (!prev_mask && !packed_out && !pruned_out) return;
+  const DevProblem p = e.p;
+  const int64_t rows = e.rows;
+  uint8_t* mask = e.mask;
+  const bool use_prev = prev_mask && e.hdr->use_prev;
   const int64_t per_row = p.cols / 8;
   for (int64_t r = blockIdx.y; r < rows; r += gridDim.y)
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < per_row; v += (int64_t)gridDim.x * blockDim.x) {
@@ -189,15 +208,21 @@ __global__ __launch_bounds__(256) void emit_kernel(DevProblem p, int64_t rows, c
 // Algorithm 2 lines 7-13 and the mask write.  M lanes per block (lane r owns row r and column r of the
 // block as bit masks), 64/M blocks per wave, one wave per workgroup.
 template <int M>
-__global__ __launch_bounds__(kWave) void finalize_kernel(DevProblem p, const block_mask_t<M>* rowmask, uint8_t* mask,
-                                                         WsHeader* hdr, int wide_store, double* block_objective,
-                                                         const uint8_t* prev_mask) {
+__global__ __launch_bounds__(kWave) void finalize_kernel(Batch batch) {
   using mask_t = block_mask_t<M>;
   constexpr int MM = M * M, G = kWave / M;
+  const int which = find_problem(batch, blockIdx.x);
+  const DevProblem p = batch.e[which].p;
+  const mask_t* rowmask = static_cast<const mask_t*>(batch.e[which].rowmask);
+  uint8_t* mask = batch.e[which].mask;
+  WsHeader* hdr = batch.e[which].hdr;
+  const int wide_store = batch.e[which].wide_store;
+  double* block_objective = batch.e[which].block_objective;
+  const uint8_t* prev_mask = batch.e[which].prev_mask;
   __shared__ float imp[G][MM];
   __shared__ mask_t rowm[G][M], colm[G][M];  // rowm[r] bit c == colm[c] bit r == S[r][c]
   const int lane = threadIdx.x, g = lane / M, ql = lane % M;
-  int64_t blk = (int64_t)blockIdx.x * G + g;
+  int64_t blk = (int64_t)(blockIdx.x - batch.first[which]) * G + g;
   const bool active = blk < p.nblocks;
   if (!active) blk = p.nblocks - 1;  // idle groups shadow the last block and write nothing
   const int64_t r0 = (blk / p.bc) * M, c0 = (blk % p.bc) * M;

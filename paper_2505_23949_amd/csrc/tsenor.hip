@@ -12,6 +12,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <vector>
 
 #include "dykstra_sort.hpp"
 #include "problem.hpp"
@@ -22,7 +23,9 @@ namespace {
 
 using namespace tsenor_dev;
 
-__global__ void init_kernel(WsHeader* hdr) {
+__global__ void init_kernel(Batch batch) {
+  if ((int)threadIdx.x >= batch.count) return;
+  WsHeader* hdr = batch.e[threadIdx.x].hdr;
   hdr->max_bits = 0u;
   hdr->use_prev = 0u;
   hdr->objective[0] = hdr->objective[1] = 0.0;
@@ -30,13 +33,17 @@ __global__ void init_kernel(WsHeader* hdr) {
   for (int k = 0; k < 4; ++k) hdr->stats[k] = 0ull;
 }
 
-// Largest importance of the matrix (App. B.1 parameter choice, relative tau).
-// Largest importance of the matrix.  VEC: every thread reads 8 consecutive weights of a row with 16-byte
-// loads (needs cols % 8 == 0 and 16-byte aligned rows and column scale); otherwise one weight at a time.
-template <bool VEC>
-__global__ __launch_bounds__(256) void absmax_kernel(DevProblem p, int64_t rows, WsHeader* hdr) {
+// Largest importance of every matrix of the batch that uses the relative tau (App. B.1 parameter choice).
+// blockIdx.z: matrix; x and y stride over its columns and rows.  With absmax_vec every thread reads 8
+// consecutive weights of a row with 16-byte loads (needs cols % 8 == 0 and 16-byte aligned rows and column
+// scale); otherwise one weight at a time.
+__global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
+  const BatchEntry& e = batch.e[blockIdx.z];
+  const DevProblem p = e.p;
+  if (p.tau_mode != TSENOR_TAU_REL_MATRIX_MAX) return;
+  const int64_t rows = e.rows;
   float m = 0.0f;
-  if constexpr (VEC) {
+  if (e.absmax_vec) {
     const int64_t vpr = p.cols / 8;  // 8-weight vectors per row
     for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
       for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < vpr; v += (int64_t)gridDim.x * blockDim.x) {
@@ -78,7 +85,7 @@ __global__ __launch_bounds__(256) void absmax_kernel(DevProblem p, int64_t rows,
   __syncthreads();
   if (threadIdx.x == 0) {
     m = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
-    atomicMax(&hdr->max_bits, __float_as_uint(m));
+    atomicMax(&e.hdr->max_bits, __float_as_uint(m));
   }
 }
 
@@ -87,8 +94,9 @@ __global__ void fill_kernel(uint8_t* mask, int64_t total, uint8_t value) {
     mask[k] = value;
 }
 
-__global__ void stats_kernel(const WsHeader* hdr, int64_t* stats_out) {
-  for (int k = 0; k < 4; ++k) stats_out[k] = (int64_t)hdr->stats[k];
+__global__ void stats_kernel(Batch batch) {
+  const int which = threadIdx.x / 4, k = threadIdx.x % 4;
+  if (which < batch.count && batch.e[which].stats_out) batch.e[which].stats_out[k] = (int64_t)batch.e[which].hdr->stats[k];
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -136,97 +144,22 @@ int validate(const tsenor_problem* p) {
   return TSENOR_OK;
 }
 
-template <int M>
-int launch_all(const DevProblem& dp, int64_t rows, const tsenor_problem& p, char* ws, const WsLayout& l,
-               hipStream_t stream, hipEvent_t* ev) {
-  // ev (optional): TSENOR_NUM_STAGES + 1 events recorded at the stage boundaries
-  auto mark = [&](int k) {
-    if (ev) (void)hipEventRecord(ev[k], stream);
-  };
-  mark(0);
-  WsHeader* hdr = reinterpret_cast<WsHeader*>(ws + l.header);
-  unsigned short* order = reinterpret_cast<unsigned short*>(ws + l.order);
-  block_mask_t<M>* accept = reinterpret_cast<block_mask_t<M>*>(ws + l.accept);
-  init_kernel<<<1, 1, 0, stream>>>(hdr);
-  if (dp.tau_mode == TSENOR_TAU_REL_MATRIX_MAX) {
-    const size_t esize = dp.dtype == TSENOR_BF16 ? 2 : 4;
-    const bool vec = dp.cols % 8 == 0 && reinterpret_cast<uintptr_t>(dp.W) % 16 == 0 && (dp.ld * esize) % 16 == 0 &&
-                     reinterpret_cast<uintptr_t>(dp.col_scale) % 16 == 0 && !dp.add && !dp.square;
-    const int64_t per_row = vec ? dp.cols / 8 : dp.cols;
-    const unsigned gx = (unsigned)std::min<int64_t>((per_row + 255) / 256, 16);
-    const dim3 grid(gx, (unsigned)std::min<int64_t>(rows, std::max<unsigned>(1024 / gx, 1)));  // ~1024 workgroups
-    if (vec)
-      absmax_kernel<true><<<grid, 256, 0, stream>>>(dp, rows, hdr);
-    else
-      absmax_kernel<false><<<grid, 256, 0, stream>>>(dp, rows, hdr);
-  }
-  mark(1);
-  constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
-  const int64_t waves = (dp.nblocks + BPW - 1) / BPW;
-  if (dp.T == 0) {
-    using L = DykstraLaunch<M, false>;
-    dykstra_sort_kernel<M, false, true><<<(unsigned)((waves + L::kWavesPerGroup - 1) / L::kWavesPerGroup),
-                                          L::kThreads, 0, stream>>>(dp, hdr, order, p.plan_out, p.tau_eff_out);
-  } else if (p.flags & TSENOR_FLAG_FP32_ITERATIONS) {
-    using L = DykstraLaunch<M, true>;
-    dykstra_sort_kernel<M, true><<<(unsigned)((waves + L::kWavesPerGroup - 1) / L::kWavesPerGroup), L::kThreads, 0,
-                                   stream>>>(dp, hdr, order, p.plan_out, p.tau_eff_out);
-  } else {
-    using L = DykstraLaunch<M, false>;
-    dykstra_sort_kernel<M, false><<<(unsigned)((waves + L::kWavesPerGroup - 1) / L::kWavesPerGroup), L::kThreads, 0,
-                                    stream>>>(dp, hdr, order, p.plan_out, p.tau_eff_out);
-  }
-  mark(2);
-  greedy_kernel<M><<<(unsigned)((dp.nblocks + kWave - 1) / kWave), kWave, 0, stream>>>(order, dp.nblocks, dp.N,
-                                                                                      accept, hdr);
-  mark(3);
-  constexpr int G = kWave / M;
-  const int wide = reinterpret_cast<uintptr_t>(p.mask) % 16 == 0;
-  const bool want_objective = p.objective_out || p.prev_mask;
-  double* block_objective = want_objective ? reinterpret_cast<double*>(ws + l.objective) : nullptr;
-  finalize_kernel<M><<<(unsigned)((dp.nblocks + G - 1) / G), kWave, 0, stream>>>(dp, accept, p.mask, hdr, wide,
-                                                                                  block_objective, p.prev_mask);
-  if (want_objective)
-    objective_kernel<<<1, 1024, 0, stream>>>(block_objective, dp.nblocks, p.prev_mask != nullptr, hdr, p.objective_out);
-  if (p.packed_out || p.pruned_out || p.prev_mask) {
-    const int64_t per_row = dp.cols / 8;
-    const unsigned gx = (unsigned)std::min<int64_t>((per_row + 255) / 256, 16);
-    const dim3 grid(gx, (unsigned)std::min<int64_t>(rows, std::max<unsigned>(2048 / gx, 1)));
-    emit_kernel<<<grid, 256, 0, stream>>>(dp, rows, hdr, p.mask, p.prev_mask, p.packed_out, p.pruned_out);
-  }
-  if (p.stats_out) stats_kernel<<<1, 1, 0, stream>>>(hdr, p.stats_out);
-  mark(4);
-  return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
+inline bool degenerate(const tsenor_problem& p) { return p.N == 0 || p.N == p.M; }
+
+// kernel variant of a problem: problems with the same variant can share one fused launch
+struct Variant {
+  int M;
+  bool fast, zero_t;
+  bool operator==(const Variant& o) const { return M == o.M && fast == o.fast && zero_t == o.zero_t; }
+};
+inline Variant variant_of(const tsenor_problem& p) {
+  return {p.M, p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0, p.iters == 0};
 }
 
-int run_one(const tsenor_problem& p, char* ws, hipStream_t stream, hipEvent_t* ev = nullptr) {
-  const int64_t total = p.rows * p.cols;
-  if (p.N == 0 || p.N == p.M) {
-    const int grid = (int)std::min<int64_t>((total + 255) / 256, 65535);
-    if (ev)
-      for (int k = 0; k < 4; ++k) (void)hipEventRecord(ev[k], stream);
-    fill_kernel<<<grid, 256, 0, stream>>>(p.mask, total, p.N == 0 ? 0 : 1);
-    // the mask of a degenerate problem needs no solve; stats are zero
-    WsHeader* hdr = reinterpret_cast<WsHeader*>(ws);
-    init_kernel<<<1, 1, 0, stream>>>(hdr);
-    if (p.stats_out) stats_kernel<<<1, 1, 0, stream>>>(hdr, p.stats_out);
-    if (p.packed_out || p.pruned_out) {
-      DevProblem dq = {};
-      dq.W = p.W;
-      dq.add = p.add;
-      dq.add_scale = p.add ? p.add_scale : 0.0f;
-      dq.ld = p.ld;
-      dq.cols = p.cols;
-      dq.dtype = p.dtype;
-      const int64_t per_row = p.cols / 8;
-      const unsigned gx = (unsigned)std::min<int64_t>((per_row + 255) / 256, 16);
-      const dim3 egrid(gx, (unsigned)std::min<int64_t>(p.rows, std::max<unsigned>(2048 / gx, 1)));
-      emit_kernel<<<egrid, 256, 0, stream>>>(dq, p.rows, hdr, p.mask, nullptr, p.packed_out, p.pruned_out);
-    }
-    if (ev) (void)hipEventRecord(ev[4], stream);
-    return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
-  }
-  DevProblem dp;
+BatchEntry entry_of(const tsenor_problem& p, char* ws) {
+  const WsLayout l = layout_of(p);
+  BatchEntry e = {};
+  DevProblem& dp = e.p;
   dp.W = p.W;
   dp.add = p.add;
   dp.add_scale = p.add ? p.add_scale : 0.0f;
@@ -244,15 +177,132 @@ int run_one(const tsenor_problem& p, char* ws, hipStream_t stream, hipEvent_t* e
   dp.strict = (p.flags & TSENOR_FLAG_STRICT_PAPER) ? 1 : 0;
   dp.tau = p.tau;
   dp.tau_mode = p.tau_mode;
-  const WsLayout l = layout_of(p);
-  switch (p.M) {
-    case 4: return launch_all<4>(dp, p.rows, p, ws, l, stream, ev);
-    case 8: return launch_all<8>(dp, p.rows, p, ws, l, stream, ev);
-    case 16: return launch_all<16>(dp, p.rows, p, ws, l, stream, ev);
-    case 32: return launch_all<32>(dp, p.rows, p, ws, l, stream, ev);
-    case 64: return launch_all<64>(dp, p.rows, p, ws, l, stream, ev);
+  e.rows = p.rows;
+  e.hdr = reinterpret_cast<WsHeader*>(ws + l.header);
+  e.order = reinterpret_cast<unsigned short*>(ws + l.order);
+  e.rowmask = ws + l.accept;
+  e.block_objective = (p.objective_out || p.prev_mask) ? reinterpret_cast<double*>(ws + l.objective) : nullptr;
+  e.mask = p.mask;
+  e.plan_out = p.plan_out;
+  e.tau_eff_out = p.tau_eff_out;
+  e.stats_out = p.stats_out;
+  e.packed_out = p.packed_out;
+  e.pruned_out = p.pruned_out;
+  e.objective_out = p.objective_out;
+  e.prev_mask = p.prev_mask;
+  e.wide_store = reinterpret_cast<uintptr_t>(p.mask) % 16 == 0;
+  const size_t esize = p.dtype == TSENOR_BF16 ? 2 : 4;
+  e.absmax_vec = p.cols % 8 == 0 && reinterpret_cast<uintptr_t>(p.W) % 16 == 0 && ((size_t)p.ld * esize) % 16 == 0 &&
+                 reinterpret_cast<uintptr_t>(p.col_scale) % 16 == 0 && !p.add && !dp.square;
+  return e;
+}
+
+// grid of the kernels that stride over a matrix 8 weights (or 1) at a time: x over a row, y over rows,
+// about `target` workgroups in all, sized for the largest matrix of the batch
+dim3 strided_grid(const Batch& b, bool vec_only, unsigned target) {
+  unsigned gx = 1, gy = 1;
+  for (int k = 0; k < b.count; ++k) {
+    const BatchEntry& e = b.e[k];
+    const int64_t per_row = (vec_only || e.absmax_vec) ? e.p.cols / 8 : e.p.cols;
+    const unsigned x = (unsigned)std::min<int64_t>((per_row + 255) / 256, 16);
+    gx = std::max(gx, x);
+    gy = std::max(gy, (unsigned)std::min<int64_t>(e.rows, std::max<unsigned>(target / x, 1)));
+  }
+  return dim3(gx, gy, (unsigned)b.count);
+}
+
+// prefix of workgroup counts when every matrix gets ceil(units / per_group) workgroups; false on overflow
+bool assign_groups(Batch& b, int64_t (*units)(const BatchEntry&), int64_t per_group) {
+  int64_t total = 0;
+  for (int k = 0; k < b.count; ++k) {
+    b.first[k] = (unsigned)total;
+    total += (units(b.e[k]) + per_group - 1) / per_group;
+    if (total > 0x7FFFFFFF) return false;
+  }
+  for (int k = b.count; k <= kMaxBatch; ++k) b.first[k] = (unsigned)total;
+  return true;
+}
+
+// All kernels of one fused launch: `b.count` non-degenerate problems of the same variant.
+// ev (optional): TSENOR_NUM_STAGES + 1 events recorded at the stage boundaries.
+template <int M>
+int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev) {
+  auto mark = [&](int k) {
+    if (ev) (void)hipEventRecord(ev[k], stream);
+  };
+  bool any_rel = false, any_objective = false, any_emit = false, any_stats = false;
+  for (int k = 0; k < b.count; ++k) {
+    const BatchEntry& e = b.e[k];
+    any_rel |= e.p.tau_mode == TSENOR_TAU_REL_MATRIX_MAX;
+    any_objective |= e.block_objective != nullptr;
+    any_emit |= e.packed_out || e.pruned_out || e.prev_mask;
+    any_stats |= e.stats_out != nullptr;
+  }
+  mark(0);
+  init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
+  if (any_rel) absmax_kernel<<<strided_grid(b, false, 1024), 256, 0, stream>>>(b);
+  mark(1);
+  constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
+  const auto blocks = [](const BatchEntry& e) { return e.p.nblocks; };
+  if (v.fast) {
+    using L = DykstraLaunch<M, true>;
+    if (!assign_groups(b, blocks, (int64_t)BPW * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
+    dykstra_sort_kernel<M, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
+  } else {
+    using L = DykstraLaunch<M, false>;
+    if (!assign_groups(b, blocks, (int64_t)BPW * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
+    if (v.zero_t)
+      dykstra_sort_kernel<M, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
+    else
+      dykstra_sort_kernel<M, false><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
+  }
+  mark(2);
+  if (!assign_groups(b, blocks, kWave)) return TSENOR_ERR_SHAPE;
+  greedy_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
+  mark(3);
+  if (!assign_groups(b, blocks, kWave / M)) return TSENOR_ERR_SHAPE;
+  finalize_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
+  if (any_objective) objective_kernel<<<b.count, 1024, 0, stream>>>(b);
+  if (any_emit) emit_kernel<<<strided_grid(b, true, 2048), 256, 0, stream>>>(b);
+  if (any_stats) stats_kernel<<<1, 4 * kMaxBatch, 0, stream>>>(b);
+  mark(4);
+  return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
+}
+
+int run_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev = nullptr) {
+  switch (v.M) {
+    case 4: return launch_group<4>(b, v, stream, ev);
+    case 8: return launch_group<8>(b, v, stream, ev);
+    case 16: return launch_group<16>(b, v, stream, ev);
+    case 32: return launch_group<32>(b, v, stream, ev);
+    case 64: return launch_group<64>(b, v, stream, ev);
   }
   return TSENOR_ERR_UNSUPPORTED;
+}
+
+// N = 0 and N = M need no solve: the mask is constant and the statistics are zero.
+int run_degenerate(const tsenor_problem& p, char* ws, hipStream_t stream, hipEvent_t* ev = nullptr) {
+  const int64_t total = p.rows * p.cols;
+  const int grid = (int)std::min<int64_t>((total + 255) / 256, 65535);
+  if (ev)
+    for (int k = 0; k < 4; ++k) (void)hipEventRecord(ev[k], stream);
+  fill_kernel<<<grid, 256, 0, stream>>>(p.mask, total, p.N == 0 ? 0 : 1);
+  Batch b = {};
+  b.count = 1;
+  b.e[0] = entry_of(p, ws);
+  init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
+  if (p.stats_out) stats_kernel<<<1, 4 * kMaxBatch, 0, stream>>>(b);
+  if (p.packed_out || p.pruned_out) emit_kernel<<<strided_grid(b, true, 2048), 256, 0, stream>>>(b);
+  if (ev) (void)hipEventRecord(ev[4], stream);
+  return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
+}
+
+int run_one(const tsenor_problem& p, char* ws, hipStream_t stream, hipEvent_t* ev = nullptr) {
+  if (degenerate(p)) return run_degenerate(p, ws, stream, ev);
+  Batch b = {};
+  b.count = 1;
+  b.e[0] = entry_of(p, ws);
+  return run_group(b, variant_of(p), stream, ev);
 }
 
 }  // namespace
@@ -280,11 +330,34 @@ int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspa
   }
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) || workspace_bytes < need)
     return TSENOR_ERR_WORKSPACE;
-  char* ws = static_cast<char*>(workspace);
+  char* const base = static_cast<char*>(workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // workspace slice of every problem, in the order given
+  std::vector<size_t> offset((size_t)count);
+  size_t at = 0;
   for (int k = 0; k < count; ++k) {
-    const int rc = run_one(problems[k], ws, static_cast<hipStream_t>(stream));
+    offset[(size_t)k] = at;
+    at += layout_of(problems[k]).total;
+  }
+  // problems that run the same kernel variant share fused launches, up to kMaxBatch matrices each
+  std::vector<char> done((size_t)count, 0);
+  for (int k = 0; k < count; ++k) {
+    if (done[(size_t)k]) continue;
+    if (degenerate(problems[k])) {
+      const int rc = run_degenerate(problems[k], base + offset[(size_t)k], s);
+      if (rc != TSENOR_OK) return rc;
+      done[(size_t)k] = 1;
+      continue;
+    }
+    const Variant v = variant_of(problems[k]);
+    Batch b = {};
+    for (int j = k; j < count && b.count < kMaxBatch; ++j) {
+      if (done[(size_t)j] || degenerate(problems[j]) || !(variant_of(problems[j]) == v)) continue;
+      b.e[b.count++] = entry_of(problems[j], base + offset[(size_t)j]);
+      done[(size_t)j] = 1;
+    }
+    const int rc = run_group(b, v, s);
     if (rc != TSENOR_OK) return rc;
-    ws += layout_of(problems[k]).total;
   }
   return TSENOR_OK;
 }

@@ -204,6 +204,77 @@ def test_batched_entry_point(dev):
         assert np.array_equal(m.cpu().numpy(), ref["mask"])
 
 
+def test_batched_mixed_variants_match_single_calls(dev):
+    # 21 problems in one call: more than one fused launch holds, several block sizes and kernel variants
+    # (fp32 iterations, T = 0), degenerate N, both tau modes and dtypes, every optional output on some of them.
+    # Every problem must come out exactly as from a call of its own, and the default variants as from the oracle.
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    rng = np.random.default_rng(4242)
+    shapes = [(64, 96), (32, 32), (96, 160), (160, 64), (64, 64), (128, 32), (32, 224)]
+    specs = []
+    for k in range(21):
+        M = (32, 16, 32, 32, 64, 32, 8)[k % 7]
+        rows, cols = shapes[k % 7]
+        rows, cols = -(-rows // M) * M, -(-cols // M) * M
+        N = M // 2 if k % 5 else (M // 4 + 1)
+        flags, iters = 0, 25 + k
+        if k in (3, 10):
+            flags = binding.TSENOR_FLAG_FP32_ITERATIONS
+        if k in (5, 12):
+            iters = 0
+        if k == 8:
+            N = 0
+        if k == 15:
+            N = M
+        specs.append(dict(M=M, N=N, rows=rows, cols=cols, flags=flags, iters=iters, bf16=k % 3 == 1,
+                          rel=k % 4 != 2, outputs=k % 2 == 0 and N not in (0, M)))
+    keep, probs, singles, outs = [], [], [], []
+    for k, s in enumerate(specs):
+        Wf = (0.02 * rng.standard_normal((s["rows"], s["cols"]))).astype(np.float32)
+        cs = rng.lognormal(0.0, 1.0, s["cols"]).astype(np.float32)
+        W = torch.from_numpy(Wf).to(dev)
+        if s["bf16"]:
+            W = W.to(torch.bfloat16)
+            Wf = W.float().cpu().numpy()
+        csd = torch.from_numpy(cs).to(dev)
+        tau, mode = (0.01, binding.TSENOR_TAU_REL_MATRIX_MAX) if s["rel"] else (40.0, binding.TSENOR_TAU_ABSOLUTE)
+        o = {"mask": torch.empty(W.shape, dtype=torch.uint8, device=dev)}
+        kw = {}
+        if s["outputs"]:
+            o["plan"] = torch.empty(W.shape, dtype=torch.float64, device=dev)
+            o["stats"] = torch.zeros(4, dtype=torch.int64, device=dev)
+            o["tau_eff"] = torch.zeros(1, dtype=torch.float64, device=dev)
+            o["packed"] = torch.empty((s["rows"], s["cols"] // 8), dtype=torch.uint8, device=dev)
+            o["pruned"] = torch.empty_like(W)
+            o["objective"] = torch.zeros(2, dtype=torch.float64, device=dev)
+            kw = dict(plan_out=o["plan"], stats_out=o["stats"], tau_eff_out=o["tau_eff"], packed_out=o["packed"],
+                      pruned_out=o["pruned"], objective_out=o["objective"])
+        probs.append(binding.make_problem(W, s["N"], s["M"], tau, s["iters"], mask=o["mask"], col_scale=csd,
+                                          tau_mode=mode, flags=s["flags"], **kw))
+        single = binding.solve(W, s["N"], s["M"], tau, s["iters"], col_scale=csd, tau_mode=mode, flags=s["flags"],
+                               want_plan=s["outputs"], want_stats=s["outputs"], want_packed=s["outputs"],
+                               want_pruned=s["outputs"], want_objective=s["outputs"])
+        keep += [W, csd]
+        outs.append(o)
+        singles.append((single, Wf, cs, tau, mode))
+    work = torch.empty(binding.tsenor_workspace_bytes(probs), dtype=torch.uint8, device=dev)
+    print(f"[case] mixed batch of {len(probs)} problems", flush=True)
+    binding.tsenor_mask_batched(probs, work)
+    torch.cuda.synchronize()
+    for k, (s, o, (single, Wf, cs, tau, mode)) in enumerate(zip(specs, outs, singles)):
+        assert torch.equal(o["mask"], single["mask"]), k
+        if s["outputs"]:
+            for name in ("plan", "stats", "tau_eff", "packed", "pruned", "objective"):
+                assert torch.equal(o[name], single[name]), (k, name)
+        if s["flags"] == 0:
+            ref = oracle.mask(Wf, s["N"], s["M"], tau, s["iters"], col_scale=cs,
+                              tau_mode=oracle.TAU_REL_MATRIX_MAX if s["rel"] else oracle.TAU_ABSOLUTE)
+            assert np.array_equal(o["mask"].cpu().numpy(), ref["mask"]), k
+
+
 def test_side_stream(dev):
     import torch
 
