@@ -14,12 +14,14 @@
 //
 // Precision.  Default: everything in double (MI355X issues fp64 vector operations at 16 lanes/clk/SIMD),
 // which reproduces a double-precision reference to ~1e-13.  FAST: the first kWarmIters iterations in
-// double, then the loop in fp32 (twice the issue rate) on kappa32 = fl32(kappa U V) with fp32 scalings
-// relative to the double ones.  fp32 has 8 exponent bits, so every kChunk iterations the relative
-// scalings are checked and, when one has drifted past 2^+-kDriftBits, folded back into the double ones
-// and kappa32 is rebuilt from the double kappa kept in LDS.  Entries are clamped to [2^-120, 2^80] when
-// they are rebuilt; within the drift bound (2^+-80 for a product of a row and a column scaling) a
-// clamped entry is still >= 1 (capped) or <= 2^-40 (nothing).
+// double, then the loop in fp32 (a shorter instruction, and half the registers: four waves per SIMD
+// instead of two) on kappa32 = fl32(kappa U V) with fp32 scalings relative to the double ones, which are
+// kept as logarithms.  fp32 has 8 exponent bits, so every kChunk iterations the relative scalings are
+// checked and, when one has drifted past 2^+-kDriftBits, their logarithms are added to the double ones and
+// kappa32 is rebuilt as fl32(exp(K - max K + log U + log V)) from a fresh read of the importance (kappa
+// itself is not kept: the fp32 phase must fit 128 registers).  Rebuilt entries are clamped to about
+// [2^-120, 2^80]; within the drift bound (2^+-80 for a product of a row and a column scaling) a clamped
+// entry is still >= 1 (capped) or <= 2^-40 (nothing).
 //
 // Layout.  A block is spread over LPB = GX*GY lanes as a GY x GX grid of TH x TW register tiles
 // (TH = M/GY rows, TW = M/GX columns); a wave holds 64/LPB blocks.  Row sums are reduced across the GX
@@ -38,6 +40,8 @@ constexpr int kIdxBits = 12;              // flat index within a block: up to 64
 constexpr int kWarmIters = 8;             // FAST: iterations done in double before switching to fp32
 constexpr int kChunk = 8;                 // FAST: iterations between range checks of the fp32 scalings
 constexpr int kDriftBits = 40;            // FAST: fold the fp32 scalings back beyond 2^+-kDriftBits
+constexpr double kLogFloor32 = -83.0;     // FAST: rebuilt entries are kept within [e^-83, e^55] ~ [2^-120, 2^80]
+constexpr double kLogCeil32 = 55.0;
 
 constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 
@@ -310,16 +314,19 @@ __device__ __forceinline__ void sort_ascending(double (&c)[E], int q) {
 
 template <int M, bool FAST>
 struct DykstraLaunch {
-  // FAST keeps a double copy of kappa in LDS (E x 64 doubles per wave); M = 64 uses two-wave workgroups
-  // so that two workgroups still fit a CU
-  static constexpr int kWavesPerGroup = (FAST && M == 64) ? 2 : 4;
+  static constexpr int kWavesPerGroup = 4;
   static constexpr int kThreads = kWavesPerGroup * kWave;
+  // waves per SIMD the register budget is set for: the fp32 loop needs four waves to keep the vector ALU
+  // issuing every other cycle (one wave issues at most every ~5 cycles); its tile fits 128 registers up to
+  // M = 32.  The double-precision loop holds twice the state: two waves of up to 256 registers.
+  static constexpr int kWavesPerSimd = (FAST && M <= 32) ? 4 : 2;
 };
 
 // ZERO_T: the instantiation for T = 0 (no iterations, keys are K itself).  It is a template parameter
 // rather than a branch because keeping both paths in one kernel costs the iterating path ~40 registers.
 template <int M, bool FAST, bool ZERO_T = false>
-__global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), 2) void dykstra_sort_kernel(Batch batch) {
+__global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<M, FAST>::kWavesPerSimd)) void dykstra_sort_kernel(
+    Batch batch) {
   using T = Tiling<M>;
   const int which = find_problem(batch, blockIdx.x);
   const DevProblem p = batch.e[which].p;
@@ -331,7 +338,6 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), 2) void dykstra
   constexpr int GX = 1 << T::NX, GY = 1 << T::NY, TH = M / GY, TW = M / GX, LPB = GX * GY, BPW = kWave / LPB,
                 E = TH * TW, SHX = ilog2(TH) - T::NX, WPG = DykstraLaunch<M, FAST>::kWavesPerGroup;
   static_assert(TH >= GX && TW >= GY, "every lane must end a reduce-scatter with at least one sum");
-  __shared__ double kap_lds[FAST ? WPG : 1][FAST ? E : 1][FAST ? kWave : 1];
   const int lane = threadIdx.x & (kWave - 1), wave_in_group = threadIdx.x / kWave;
   const int64_t wave = (int64_t)group * WPG + wave_in_group;
   const int q = lane % LPB, gx = q % GX, gy = q / GX;
@@ -402,41 +408,84 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), 2) void dykstra
 #pragma unroll
       for (int b = 0; b < TW; ++b) {
         kap[a][b] = exp(fmax(kap[a][b] - mx, kMinLogKernel));
-        if constexpr (FAST) kap_lds[wave_in_group][a * TW + b][lane] = kap[a][b];
         __builtin_amdgcn_sched_barrier(0);  // one exp at a time: interleaving them only costs registers
       }
 
     const double Nd = (double)p.N;
-    double U[TH], V[TW];
+    // logs of the scalings of the rows and columns this lane owns (the first registers after a
+    // reduce-scatter); the other lanes of the lane-row / lane-column hold the same values for theirs
+    constexpr int OWN_R = TH >> T::NX, OWN_C = TW >> T::NY;
+    double lu_own[OWN_R], lv_own[OWN_C];
+    {
+      double U[TH], V[TW];
 #pragma unroll
-    for (int a = 0; a < TH; ++a) U[a] = 1.0;
+      for (int a = 0; a < TH; ++a) U[a] = 1.0;
 #pragma unroll
-    for (int b = 0; b < TW; ++b) V[b] = 1.0;
-
-    const int t_double = FAST ? (p.T < kWarmIters ? p.T : kWarmIters) : p.T;
-    for (int t = 0; t < t_double; ++t) dykstra_iteration<T, T::STORE_E>(kap, U, V, Nd, 1e-300);
+      for (int b = 0; b < TW; ++b) V[b] = 1.0;
+      if constexpr (FAST) {
+        // the entries are recomputed in the column pass: this phase must fit the registers of the fp32 loop
+        const int t_double = p.T < kWarmIters ? p.T : kWarmIters;
+        for (int t = 0; t < t_double; ++t) dykstra_iteration<T, false>(kap, U, V, Nd, 1e-300);
+      } else {
+        for (int t = 0; t < p.T; ++t) dykstra_iteration<T, T::STORE_E>(kap, U, V, Nd, 1e-300);
+      }
+#pragma unroll
+      for (int a = 0; a < OWN_R; ++a) {
+        lu_own[a] = log(U[a]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int b = 0; b < OWN_C; ++b) {
+        lv_own[b] = log(V[b]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
 
     if constexpr (FAST) {
-      if (p.T > t_double) {
-        // fp32 phase: kap32 = fl32(kap U V), scalings U32, V32 relative to the double ones
+      if (p.T > kWarmIters) {
+        // fp32 phase: kap32 = fl32(kap U V) for the double scalings U V reached so far, and fp32 scalings
+        // U32, V32 relative to them.  kap is not kept: a rebuild reloads the importance.
         float kap32[TH][TW], U32[TH], Uinv32[TH], V32[TW];
         const float Nf = (float)p.N;
         const float hi = __builtin_ldexpf(1.0f, kDriftBits), lo = __builtin_ldexpf(1.0f, -kDriftBits);
         auto rebuild = [&]() {
+          const int rx1 = fresh(rx), ry1 = fresh(ry);
+          double lu[TH], lv[TW];
+#pragma unroll
+          for (int a = 0; a < OWN_R; ++a) lu[a] = lu_own[a];
+#pragma unroll
+          for (int b = 0; b < OWN_C; ++b) lv[b] = lv_own[b];
+          all_gather_x<T, double, TH>(lu);
+          all_gather_y<T, double, TW>(lv);
 #pragma unroll
           for (int a = 0; a < TH; ++a)
 #pragma unroll
             for (int b = 0; b < TW; ++b) {
-              const double full = (kap_lds[wave_in_group][a * TW + b][lane] * V[b]) * U[a];
-              kap32[a][b] = (float)fmin(fmax(full, 0x1p-120), 0x1p80);
+              const int ri = gy * TH + (a ^ rx1), cj = gx * TW + (b ^ ry1);
+              const double K = tau_eff * (double)load_importance(p, r0 + mat_row(ri, cj), c0 + mat_col(ri, cj));
+              const double full = fmax(K - mx, kMinLogKernel) + (lu[a] + lv[b]);
+              kap32[a][b] = (float)exp(fmin(fmax(full, kLogFloor32), kLogCeil32));
+              __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
           for (int a = 0; a < TH; ++a) U32[a] = Uinv32[a] = 1.0f;
 #pragma unroll
           for (int b = 0; b < TW; ++b) V32[b] = 1.0f;
         };
+        auto fold = [&]() {
+#pragma unroll
+          for (int a = 0; a < OWN_R; ++a) {
+            lu_own[a] += log((double)U32[a]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+#pragma unroll
+          for (int b = 0; b < OWN_C; ++b) {
+            lv_own[b] += log((double)V32[b]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        };
         rebuild();
-        for (int t = t_double; t < p.T;) {
+        for (int t = kWarmIters; t < p.T;) {
           const int stop = (p.T - t > kChunk) ? t + kChunk : p.T;
           for (; t < stop; ++t) dykstra_iteration_f32<T>(kap32, U32, Uinv32, V32, Nf);
           float mxs = U32[0], mns = U32[0];
@@ -446,32 +495,22 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), 2) void dykstra
           for (int b = 0; b < TW; ++b) mxs = fmaxf(mxs, V32[b]), mns = fminf(mns, V32[b]);
           // wave-uniform: fold the fp32 scalings into the double ones when any lane's have drifted
           if (t < p.T && __any(!(mxs < hi && mns > lo))) {
-#pragma unroll
-            for (int a = 0; a < TH; ++a) U[a] *= (double)U32[a];
-#pragma unroll
-            for (int b = 0; b < TW; ++b) V[b] *= (double)V32[b];
+            fold();
             rebuild();
           }
         }
-#pragma unroll
-        for (int a = 0; a < TH; ++a) U[a] *= (double)U32[a];
-#pragma unroll
-        for (int b = 0; b < TW; ++b) V[b] *= (double)V32[b];
+        fold();
       }
     }
 
     const int rx2 = fresh(rx), ry2 = fresh(ry);
     double lu[TH], lv[TW];
 #pragma unroll
-    for (int a = 0; a < TH; ++a) {
-      lu[a] = log(U[a]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    for (int a = 0; a < OWN_R; ++a) lu[a] = lu_own[a];
 #pragma unroll
-    for (int b = 0; b < TW; ++b) {
-      lv[b] = log(V[b]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    for (int b = 0; b < OWN_C; ++b) lv[b] = lv_own[b];
+    all_gather_x<T, double, TH>(lu);
+    all_gather_y<T, double, TW>(lv);
 #pragma unroll
     for (int a = 0; a < TH; ++a)
 #pragma unroll
