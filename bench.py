@@ -100,6 +100,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3_16of32_4096x14336")
     ap.add_argument("--rows", type=int, default=0, help="override rows (debug)")
     ap.add_argument("--cols", type=int, default=0, help="override cols (debug)")
+    ap.add_argument("--iters", type=int, default=-1, help="override the iteration count T (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
     ap.add_argument("--fp32-iterations", action="store_true",
@@ -126,6 +127,10 @@ def main() -> int:
     w = synth.CONFIGS[args.workload]
     if args.rows and args.cols:
         w = w.scaled(args.rows, args.cols)
+    if args.iters >= 0:
+        from dataclasses import replace
+
+        w = replace(w, iters=args.iters)
     dev = torch.device("cuda:0")
     g = synth.generate(w)
     if w.dtype == "bf16":

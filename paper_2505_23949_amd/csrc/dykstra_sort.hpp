@@ -30,6 +30,8 @@
 // same way.  To keep every exchange a fixed set of registers (no selects), register a of lane gx holds
 // tile row a ^ (gx << log2(TH/GX)); columns likewise over the GY lanes of a lane-column.
 #pragma once
+#include <type_traits>
+
 #include "lanes.hpp"
 #include "problem.hpp"
 
@@ -361,28 +363,36 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
   auto mat_row = [&](int ri, int cj) { return p.transpose ? cj : ri; };
   auto mat_col = [&](int ri, int cj) { return p.transpose ? ri : cj; };
 
+  // tile addressing of one phase, from that phase's copy of the lane offsets
+  auto addr_of = [&](int rxp, int ryp) {
+    int ri[TH], cj[TW];
+#pragma unroll
+    for (int a = 0; a < TH; ++a) ri[a] = gy * TH + (a ^ rxp);
+#pragma unroll
+    for (int b = 0; b < TW; ++b) cj[b] = gx * TW + (b ^ ryp);
+    return tile_addr<TH, TW>(p, r0, c0, ri, cj);
+  };
+  // the fp32 variant lives in half the registers: it loads a tile in two halves
+  constexpr int NA = (FAST && TH >= 8) ? TH / 2 : TH;
+
   double kap[TH][TW];
   double mx = 0.0;
   {
-    float imp[TH][TW];
+    const auto addr = addr_of(fresh(rx), fresh(ry));
+    auto rows = [&](auto first) {
+      constexpr int A0 = decltype(first)::value;
+      float imp[NA][TW];
+      tile_importance<A0, NA>(p, addr, imp);
 #pragma unroll
-    for (int a = 0; a < TH; ++a) {
+      for (int a = 0; a < NA; ++a)
 #pragma unroll
-      for (int b = 0; b < TW; ++b) {
-        const int ri = gy * TH + (a ^ rx), cj = gx * TW + (b ^ ry);
-        imp[a][b] = load_importance(p, r0 + mat_row(ri, cj), c0 + mat_col(ri, cj));
-      }
-      // one tile row of loads at a time: scheduling all address computations first costs more registers
-      // than the kernel has
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int a = 0; a < TH; ++a)
-#pragma unroll
-      for (int b = 0; b < TW; ++b) {
-        kap[a][b] = tau_eff * (double)imp[a][b];  // K of Algorithm 1 line 1
-        mx = fmax(mx, kap[a][b]);
-      }
+        for (int b = 0; b < TW; ++b) {
+          kap[A0 + a][b] = tau_eff * (double)imp[a][b];  // K of Algorithm 1 line 1
+          mx = fmax(mx, kap[A0 + a][b]);
+        }
+    };
+    rows(std::integral_constant<int, 0>{});
+    if constexpr (NA < TH) rows(std::integral_constant<int, NA>{});
   }
   mx = group_max<LPB>(mx);
 
@@ -457,16 +467,23 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
           for (int b = 0; b < OWN_C; ++b) lv[b] = lv_own[b];
           all_gather_x<T, double, TH>(lu);
           all_gather_y<T, double, TW>(lv);
+          const auto addr = addr_of(rx1, ry1);
+          auto rows = [&](auto first) {
+            constexpr int A0 = decltype(first)::value;
+            float imp[NA][TW];
+            tile_importance<A0, NA>(p, addr, imp);
 #pragma unroll
-          for (int a = 0; a < TH; ++a)
+            for (int a = 0; a < NA; ++a)
 #pragma unroll
-            for (int b = 0; b < TW; ++b) {
-              const int ri = gy * TH + (a ^ rx1), cj = gx * TW + (b ^ ry1);
-              const double K = tau_eff * (double)load_importance(p, r0 + mat_row(ri, cj), c0 + mat_col(ri, cj));
-              const double full = fmax(K - mx, kMinLogKernel) + (lu[a] + lv[b]);
-              kap32[a][b] = (float)exp(fmin(fmax(full, kLogFloor32), kLogCeil32));
-              __builtin_amdgcn_sched_barrier(0);
-            }
+              for (int b = 0; b < TW; ++b) {
+                const double K = tau_eff * (double)imp[a][b];
+                const double full = fmax(K - mx, kMinLogKernel) + (lu[A0 + a] + lv[b]);
+                kap32[A0 + a][b] = (float)exp(fmin(fmax(full, kLogFloor32), kLogCeil32));
+                __builtin_amdgcn_sched_barrier(0);
+              }
+          };
+          rows(std::integral_constant<int, 0>{});
+          if constexpr (NA < TH) rows(std::integral_constant<int, NA>{});
 #pragma unroll
           for (int a = 0; a < TH; ++a) U32[a] = Uinv32[a] = 1.0f;
 #pragma unroll
@@ -511,23 +528,29 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
     for (int b = 0; b < OWN_C; ++b) lv[b] = lv_own[b];
     all_gather_x<T, double, TH>(lu);
     all_gather_y<T, double, TW>(lv);
+    const auto addr = addr_of(rx2, ry2);
+    auto rows = [&](auto first) {
+      constexpr int A0 = decltype(first)::value;
+      float imp[NA][TW];
+      tile_importance<A0, NA>(p, addr, imp);
 #pragma unroll
-    for (int a = 0; a < TH; ++a)
+      for (int a = 0; a < NA; ++a)
 #pragma unroll
-      for (int b = 0; b < TW; ++b) {
-        const int ri = gy * TH + (a ^ rx2), cj = gx * TW + (b ^ ry2);
-        const int64_t mr = r0 + mat_row(ri, cj), mc = c0 + mat_col(ri, cj);
-        const double K = tau_eff * (double)load_importance(p, mr, mc);
-        // log S^(T) = min(K + f_i + g_j, 0)
-        const double key = fmin(fmax(K - mx, kMinLogKernel) + (lu[a] + lv[b]), 0.0);
-        if (plan_out && active) plan_out[mr * p.cols + mc] = exp(key);
-        const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
-        const unsigned long long bits = (unsigned long long)__double_as_longlong(fabs(key));
-        // descending key, ties by ascending flat index; + 2^52 keeps the pattern a normal double
-        c[a * TW + b] =
-            __longlong_as_double((long long)(((bits & ~((1ull << kIdxBits) - 1)) | idx) + (1ull << 52)));
-        __builtin_amdgcn_sched_barrier(0);
-      }
+        for (int b = 0; b < TW; ++b) {
+          const int ri = gy * TH + ((A0 + a) ^ rx2), cj = gx * TW + (b ^ ry2);
+          const double K = tau_eff * (double)imp[a][b];
+          // log S^(T) = min(K + f_i + g_j, 0)
+          const double key = fmin(fmax(K - mx, kMinLogKernel) + (lu[A0 + a] + lv[b]), 0.0);
+          if (plan_out && active) plan_out[(r0 + mat_row(ri, cj)) * p.cols + c0 + mat_col(ri, cj)] = exp(key);
+          const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
+          const unsigned long long bits = (unsigned long long)__double_as_longlong(fabs(key));
+          // descending key, ties by ascending flat index; + 2^52 keeps the pattern a normal double
+          c[(A0 + a) * TW + b] =
+              __longlong_as_double((long long)(((bits & ~((1ull << kIdxBits) - 1)) | idx) + (1ull << 52)));
+        }
+    };
+    rows(std::integral_constant<int, 0>{});
+    if constexpr (NA < TH) rows(std::integral_constant<int, NA>{});
   }
 
   sort_ascending<E, LPB>(c, q);

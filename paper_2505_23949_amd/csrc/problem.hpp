@@ -91,6 +91,139 @@ __device__ __forceinline__ float load_importance(const DevProblem& p, int64_t r,
   return a;
 }
 
+// Tile loads.  A lane holds a TH x TW register tile of its block; the element offset of tile entry (a, b)
+// is base + roff[a] + coff[b], and its column scale is csa[a] * csb[b] where one of the two factors is
+// exactly 1 (which of them depends on whether the kernel works on the block or on its transpose), so the
+// product with both is still the single rounded multiply of the definition above.  The point of this form:
+// every choice (storage type, additive term, scale, transpose) is made once per tile, and the loads of a
+// tile are one straight run of independent instructions instead of a chain of branches with a wait each.
+template <int TH, int TW>
+struct TileAddr {
+  int64_t base;
+  int64_t roff[TH], coff[TW];
+  float csa[TH], csb[TW];
+};
+
+// ri[a], cj[b]: coordinates of the tile's rows and columns inside the (possibly transposed) block at
+// matrix position (r0, c0)
+template <int TH, int TW>
+__device__ __forceinline__ TileAddr<TH, TW> tile_addr(const DevProblem& p, int64_t r0, int64_t c0, const int (&ri)[TH],
+                                                      const int (&cj)[TW]) {
+  TileAddr<TH, TW> t;
+  t.base = r0 * p.ld + c0;
+#pragma unroll
+  for (int a = 0; a < TH; ++a) {
+    t.roff[a] = p.transpose ? (int64_t)ri[a] : ri[a] * p.ld;
+    t.csa[a] = 1.0f;
+  }
+#pragma unroll
+  for (int b = 0; b < TW; ++b) {
+    t.coff[b] = p.transpose ? cj[b] * p.ld : (int64_t)cj[b];
+    t.csb[b] = 1.0f;
+  }
+  if (p.col_scale) {
+    if (p.transpose) {
+#pragma unroll
+      for (int a = 0; a < TH; ++a) t.csa[a] = p.col_scale[c0 + ri[a]];
+    } else {
+#pragma unroll
+      for (int b = 0; b < TW; ++b) t.csb[b] = p.col_scale[c0 + cj[b]];
+    }
+  }
+  return t;
+}
+
+template <bool BF16, bool ADD, int A0, int NA, int TH, int TW>
+__device__ __forceinline__ void tile_values(const DevProblem& p, const TileAddr<TH, TW>& t, float (&x)[NA][TW]) {
+  float v[ADD ? NA : 1][ADD ? TW : 1];
+#pragma unroll
+  for (int a = 0; a < NA; ++a)
+#pragma unroll
+    for (int b = 0; b < TW; ++b) {
+      const int64_t off = t.base + t.roff[A0 + a] + t.coff[b];
+      if constexpr (BF16) {
+        x[a][b] = __uint_as_float((unsigned int)reinterpret_cast<const unsigned short*>(p.W)[off] << 16);
+        if constexpr (ADD) v[a][b] = __uint_as_float((unsigned int)reinterpret_cast<const unsigned short*>(p.add)[off] << 16);
+      } else {
+        x[a][b] = reinterpret_cast<const float*>(p.W)[off];
+        if constexpr (ADD) v[a][b] = reinterpret_cast<const float*>(p.add)[off];
+      }
+    }
+  if constexpr (ADD) {
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+      for (int b = 0; b < TW; ++b) x[a][b] = __fadd_rn(x[a][b], __fmul_rn(p.add_scale, v[a][b]));
+  }
+}
+
+// importance of tile rows [A0, A0 + NA): the same operations, in the same order, as load_importance
+template <int A0, int NA, int TH, int TW>
+__device__ __forceinline__ void tile_importance(const DevProblem& p, const TileAddr<TH, TW>& t, float (&imp)[NA][TW]) {
+  if (p.dtype == TSENOR_BF16) {
+    if (p.add)
+      tile_values<true, true, A0, NA>(p, t, imp);
+    else
+      tile_values<true, false, A0, NA>(p, t, imp);
+  } else {
+    if (p.add)
+      tile_values<false, true, A0, NA>(p, t, imp);
+    else
+      tile_values<false, false, A0, NA>(p, t, imp);
+  }
+#pragma unroll
+  for (int a = 0; a < NA; ++a)
+#pragma unroll
+    for (int b = 0; b < TW; ++b) {
+      float m = __fmul_rn(__fmul_rn(fabsf(imp[a][b]), t.csa[A0 + a]), t.csb[b]);
+      if (p.square) m = __fmul_rn(m, m);
+      imp[a][b] = m;
+    }
+}
+
+// importance of the M entries (r0 .. r0+M-1, c) of one matrix column, loads issued together; the same
+// operations, in the same order, as load_importance
+template <int M, bool BF16, bool ADD>
+__device__ __forceinline__ void block_column_values(const DevProblem& p, int64_t r0, int64_t c, float (&x)[M]) {
+  float v[ADD ? M : 1];
+#pragma unroll
+  for (int k = 0; k < M; ++k) {
+    const int64_t off = (r0 + k) * p.ld + c;
+    if constexpr (BF16) {
+      x[k] = __uint_as_float((unsigned int)reinterpret_cast<const unsigned short*>(p.W)[off] << 16);
+      if constexpr (ADD) v[k] = __uint_as_float((unsigned int)reinterpret_cast<const unsigned short*>(p.add)[off] << 16);
+    } else {
+      x[k] = reinterpret_cast<const float*>(p.W)[off];
+      if constexpr (ADD) v[k] = reinterpret_cast<const float*>(p.add)[off];
+    }
+  }
+  if constexpr (ADD) {
+#pragma unroll
+    for (int k = 0; k < M; ++k) x[k] = __fadd_rn(x[k], __fmul_rn(p.add_scale, v[k]));
+  }
+}
+template <int M>
+__device__ __forceinline__ void block_column_importance(const DevProblem& p, int64_t r0, int64_t c, float (&imp)[M]) {
+  if (p.dtype == TSENOR_BF16) {
+    if (p.add)
+      block_column_values<M, true, true>(p, r0, c, imp);
+    else
+      block_column_values<M, true, false>(p, r0, c, imp);
+  } else {
+    if (p.add)
+      block_column_values<M, false, true>(p, r0, c, imp);
+    else
+      block_column_values<M, false, false>(p, r0, c, imp);
+  }
+  const float cs = p.col_scale ? p.col_scale[c] : 1.0f;
+#pragma unroll
+  for (int k = 0; k < M; ++k) {
+    float m = __fmul_rn(fabsf(imp[k]), cs);  // times exactly 1 where there is no scale
+    if (p.square) m = __fmul_rn(m, m);
+    imp[k] = m;
+  }
+}
+
 // multiplier of the importance in the log-kernel K (App. B.1 parameter choice for the relative mode)
 __device__ __forceinline__ double tau_eff_of(const DevProblem& p, const WsHeader* hdr) {
   if (p.tau_mode == TSENOR_TAU_ABSOLUTE) return p.tau;

@@ -239,8 +239,12 @@ __global__ __launch_bounds__(kWave) void finalize_kernel(Batch batch) {
   const unsigned long long gmask = (M == 64 ? ~0ull : ((1ull << M) - 1)) << (g * M);
   const bool any_short = __any(popc(rowm[g][ql]) < p.N);
   if (any_short || block_objective) {
-    // local search scores on the importance (Eq. 5), staged in LDS: row k of every block per step
-    for (int k = 0; k < M; ++k) imp[g][k * M + ql] = load_importance(p, r0 + k, c0 + ql);
+    // local search scores on the importance (Eq. 5), staged in LDS: this lane fetches column ql of its
+    // block, all M loads in flight at once
+    float col[M];
+    block_column_importance<M>(p, r0, c0 + ql, col);
+#pragma unroll
+    for (int k = 0; k < M; ++k) imp[g][k * M + ql] = col[k];
   }
   __syncthreads();
 
@@ -313,11 +317,21 @@ __global__ __launch_bounds__(kWave) void finalize_kernel(Batch batch) {
       // sum S * importance of this block for the mask found and for the caller's previous mask: every lane
       // sums its row left to right, the rows are then added in a fixed butterfly order
       double mine = 0.0, theirs = 0.0;
-      const uint8_t* prev = prev_mask ? prev_mask + (r0 + ql) * p.cols + c0 : nullptr;
+      mask_t prev_bits = 0;
+      if (prev_mask) {
+        // the previous mask's row as bits: the byte loads are independent of each other
+        const uint8_t* prev = prev_mask + (r0 + ql) * p.cols + c0;
+        uint8_t pm[M];
+#pragma unroll
+        for (int k = 0; k < M; ++k) pm[k] = prev[k];
+#pragma unroll
+        for (int k = 0; k < M; ++k) prev_bits |= (mask_t)(pm[k] != 0) << k;
+      }
+#pragma unroll
       for (int k = 0; k < M; ++k) {
         const double v = (double)imp[g][ql * M + k];
-        if ((bits >> k) & 1) mine += v;
-        if (prev && prev[k]) theirs += v;
+        mine += ((bits >> k) & 1) ? v : 0.0;
+        theirs += ((prev_bits >> k) & 1) ? v : 0.0;
       }
       mine = group_sum<M>(mine);
       theirs = group_sum<M>(theirs);
