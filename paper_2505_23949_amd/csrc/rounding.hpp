@@ -23,7 +23,9 @@ __device__ __forceinline__ int mask_popc(mask_t v) {
 // Algorithm 2 lines 1-6: scan the entries of a block in sorted order and keep an entry while its row
 // and its column hold fewer than N.  The chain of M*M dependent steps runs with ONE LANE PER BLOCK, so
 // every lane of the wave does useful work; the state of a lane (M row masks, M column counters) lives in
-// LDS.  Output: the mask as M row bit masks per block (bit c of word r = S[r][c]).
+// LDS.  The kernel is bound by the instruction issue of its single wave per SIMD (~27 instructions per
+// entry), not by memory: the scan order is prefetched a cache line ahead and the LDS state of four entries
+// is fetched per round trip.  Output: the mask as M row bit masks per block (bit c of word r = S[r][c]).
 template <int M>
 __global__ __launch_bounds__(kWave) void greedy_kernel(Batch batch) {
   using mask_t = block_mask_t<M>;
@@ -47,21 +49,57 @@ __global__ __launch_bounds__(kWave) void greedy_kernel(Batch batch) {
     const unsigned short* src = order + blk * MM;
     int placed = 0;
     const int need = N * M;
-    for (int h = 0; h < MM && placed < need; h += 8) {
-      const uint4 v = *reinterpret_cast<const uint4*>(src + h);
-      const unsigned int pk[4] = {v.x, v.y, v.z, v.w};
+    // the scan order arrives 8 entries per 16-byte load; the D loads of the next 8*D entries (one 128-byte
+    // line of this lane's block for D = 8) are in flight while the current 8*D entries are decided
+    constexpr int D = MM / 8 < 8 ? MM / 8 : 8;
+    uint4 cur[D], nxt[D];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const unsigned int idx = (pk[u >> 1] >> ((u & 1) * 16)) & (unsigned)(MM - 1);
-        const unsigned int i = idx / M, j = idx % M;
-        const mask_t rb = rowbits[i][lane];
-        const unsigned int cj = colcnt[j][lane];
-        if (mask_popc(rb) < N && cj < (unsigned)N) {
-          rowbits[i][lane] = rb | ((mask_t)1 << j);
-          colcnt[j][lane] = (unsigned char)(cj + 1);
-          ++placed;
+    for (int d = 0; d < D; ++d) cur[d] = *reinterpret_cast<const uint4*>(src + 8 * d);
+    for (int h0 = 0; h0 < MM && placed < need; h0 += 8 * D) {
+      const int hn = h0 + 8 * D < MM ? h0 + 8 * D : 0;  // (the last round reads the start again, unused)
+#pragma unroll
+      for (int d = 0; d < D; ++d) nxt[d] = *reinterpret_cast<const uint4*>(src + hn + 8 * d);
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+      const uint4 v = cur[d];
+      const unsigned int pk[4] = {v.x, v.y, v.z, v.w};
+      // four entries per step: their rows' masks and columns' counters are read together (one LDS round trip
+      // instead of four), the decisions are then taken in order in registers, a later entry of the four
+      // inheriting the state of an earlier one in the same row or column
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        unsigned int i[4], j[4], cc[4];
+        mask_t rb[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const unsigned int idx = (pk[half * 2 + (k >> 1)] >> ((k & 1) * 16)) & (unsigned)(MM - 1);
+          i[k] = idx / M;
+          j[k] = idx % M;
+          rb[k] = rowbits[i[k]][lane];
+          cc[k] = colcnt[j[k]][lane];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const unsigned int take = (mask_popc(rb[k]) < N && cc[k] < (unsigned)N) ? 1u : 0u;
+          rb[k] |= (mask_t)take << j[k];
+          cc[k] += take;
+          placed += (int)take;
+#pragma unroll
+          for (int m = k + 1; m < 4; ++m) {
+            rb[m] = i[m] == i[k] ? rb[k] : rb[m];
+            cc[m] = j[m] == j[k] ? cc[k] : cc[m];
+          }
+        }
+        // written back in order: for a row or column that occurs twice the later, more complete value stays
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          rowbits[i[k]][lane] = rb[k];
+          colcnt[j[k]][lane] = (unsigned char)cc[k];
         }
       }
+      }
+#pragma unroll
+      for (int d = 0; d < D; ++d) cur[d] = nxt[d];
     }
     for (int k = 0; k < M; ++k) rowmask[blk * M + k] = rowbits[k][lane];
     missing = need - placed;
