@@ -54,11 +54,12 @@ __global__ __launch_bounds__(kWave) void greedy_kernel(Batch batch) {
     constexpr int D = MM / 8 < 8 ? MM / 8 : 8;
     uint4 cur[D], nxt[D];
 #pragma unroll
-    for (int d = 0; d < D; ++d) cur[d] = *reinterpret_cast<const uint4*>(src + 8 * d);
+    for (int d = 0; d < D; ++d) nxt[d] = cur[d] = *reinterpret_cast<const uint4*>(src + 8 * d);
     for (int h0 = 0; h0 < MM && placed < need; h0 += 8 * D) {
-      const int hn = h0 + 8 * D < MM ? h0 + 8 * D : 0;  // (the last round reads the start again, unused)
+      if (h0 + 8 * D < MM) {
 #pragma unroll
-      for (int d = 0; d < D; ++d) nxt[d] = *reinterpret_cast<const uint4*>(src + hn + 8 * d);
+        for (int d = 0; d < D; ++d) nxt[d] = *reinterpret_cast<const uint4*>(src + h0 + 8 * D + 8 * d);
+      }
 #pragma unroll
       for (int d = 0; d < D; ++d) {
       const uint4 v = cur[d];
