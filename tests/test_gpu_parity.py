@@ -454,6 +454,29 @@ def test_parity_fp32_iterations(dev, w):
     print(f"  identical blocks {same.mean():.5f} ({int((~same).sum())} differ), max plan error {err:.3e}", flush=True)
 
 
+@pytest.mark.parametrize("M,N,dtype", [(32, 16, "bf16"), (16, 8, "f32"), (64, 32, "bf16")])
+def test_fp32_iterations_columns_first_with_column_scale(dev, M, N, dtype):
+    # the rebuilds of the fp32 phase re-read the importance of the transposed block (column scale per tile row)
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.Workload(f"fp32_cols_first_{N}of{M}", 4 * M, 6 * M, N, M, 0.005, 200, dtype, "wanda", 900 + M)
+    g = synth.generate(w)
+    W, cs = _to_device(g, w, dev)
+    print(f"[case] fp32 iterations, columns first, {w.name}", flush=True)
+    res = binding.solve(W, N, M, w.tau, w.iters, col_scale=cs, tau_mode=w.tau_mode, want_plan=True,
+                        flags=binding.TSENOR_FLAG_FP32_ITERATIONS | binding.TSENOR_FLAG_COLS_FIRST)
+    torch.cuda.synchronize()
+    ref = oracle.mask(g["W_f32"], N, M, w.tau, w.iters, col_scale=g["col_scale"], tau_mode=w.tau_mode,
+                      cols_first=True, return_plan=True)
+    mask = res["mask"].cpu().numpy()
+    assert np.abs(res["plan"].cpu().numpy() - np.exp(ref["log_S"])).max() <= FP32_PLAN_ATOL
+    assert exact.is_transposable_nm(mask, N, M)
+    same = (exact.blocks(mask, M) == exact.blocks(ref["mask"], M)).all(axis=(1, 2))
+    assert same.mean() >= 0.999
+
+
 def test_full_size_sampled_parity_fp32_iterations(dev):
     import torch
 
@@ -515,9 +538,11 @@ def _bf16_to_f32_np(t):
     return synth.bf16_bits_to_f32(t.view(__import__("torch").int16).cpu().numpy().view(np.uint16))
 
 
-@pytest.mark.parametrize("dtype,N,M,square", [("f32", 8, 16, True), ("bf16", 16, 32, True), ("f32", 2, 4, False),
-                                              ("f32", 32, 64, True)])
-def test_alps_style_importance_and_outputs(dev, dtype, N, M, square):
+@pytest.mark.parametrize("dtype,N,M,square,cols_first",
+                         [("f32", 8, 16, True, False), ("bf16", 16, 32, True, False), ("f32", 2, 4, False, False),
+                          ("f32", 32, 64, True, False), ("bf16", 16, 32, False, True), ("f32", 8, 16, True, True),
+                          ("bf16", 4, 8, True, True), ("bf16", 32, 64, False, True)])
+def test_alps_style_importance_and_outputs(dev, dtype, N, M, square, cols_first):
     import torch
 
     from paper_2505_23949_amd import binding
@@ -538,13 +563,14 @@ def test_alps_style_importance_and_outputs(dev, dtype, N, M, square):
     rho = 3.0
     add_scale = float(np.float32(1.0 / rho))
     imode = binding.TSENOR_IMPORTANCE_SQUARE if square else binding.TSENOR_IMPORTANCE_ABS
-    print(f"[case] transforms {dtype} {N}:{M} square={square}", flush=True)
+    print(f"[case] transforms {dtype} {N}:{M} square={square} cols_first={cols_first}", flush=True)
     res = binding.solve(Wd, N, M, 0.01, 120, col_scale=cd, tau_mode=binding.TSENOR_TAU_REL_MATRIX_MAX, add=Vd,
                         add_scale=add_scale, importance=imode, want_plan=True, want_stats=True, want_packed=True,
-                        want_pruned=True, want_objective=True)
+                        want_pruned=True, want_objective=True,
+                        flags=binding.TSENOR_FLAG_COLS_FIRST if cols_first else 0)
     torch.cuda.synchronize()
     ref = oracle.solve_ex(W, N, M, 0.01, 120, add=V, add_scale=add_scale, col_scale=c, square=square,
-                          tau_mode=oracle.TAU_REL_MATRIX_MAX)
+                          tau_mode=oracle.TAU_REL_MATRIX_MAX, cols_first=cols_first)
     assert float(res["tau_eff"].cpu()[0]) == ref["tau_eff"]
     assert np.abs(res["plan"].cpu().numpy() - np.exp(ref["log_S"])).max() <= PLAN_ATOL
     mask = res["mask"].cpu().numpy()

@@ -1,0 +1,99 @@
+"""Solution quality of the HIP path against the exact optimum, and the ablation arms of App. B.2.1.
+
+The arms are reached through the library's own parameters: rounding the entropy solution (T > 0) or the
+importance itself (T = 0), with the full Algorithm 2 or with greedy selection only (strict mode, L = 0).
+The exact optimum of every block comes from the LP relaxation of Eq. (3) (integral: a capacitated bipartite
+b-matching), solved on the CPU.  Relative error = (f(S*) - f(S)) / f(S*) as in Fig. 3 / Fig. 5.
+
+Inputs are synthetic stand-ins for the LLaMA blocks of the paper, so the assertions are the orderings the
+paper reports (Sec. 3.3, App. B.2.1), not its percentages.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import exact
+from paper_2505_23949_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    return torch.device("cuda:0")
+
+
+def _relative_errors(mask, imp, opt, M, feasible=True):
+    got = (exact.blocks(mask, M) * exact.blocks(imp, M)).sum(axis=(1, 2))
+    if feasible:
+        # (the LP solver stops at a relative tolerance of ~1e-9; a mask with short rows, as greedy selection
+        # alone can leave, is outside the feasible set and may exceed the optimum)
+        assert np.all(got <= opt * (1 + 1e-7)), "a feasible mask cannot beat the exact optimum"
+    return (opt - got) / opt
+
+
+@pytest.mark.parametrize("N,M,block_rows,block_cols", [(4, 8, 8, 16), (8, 16, 6, 12), (16, 32, 3, 8)])
+def test_ablation_arms_against_the_exact_optimum(dev, N, M, block_rows, block_cols):
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.Workload(f"quality_{N}of{M}", block_rows * M, block_cols * M, N, M, 0.005, 300, "f32", "wanda", 3100 + M)
+    g = synth.generate(w)
+    W = torch.from_numpy(g["W_store"]).to(dev)
+    cs = torch.from_numpy(g["col_scale"]).to(dev)
+    imp = oracle.importance(g["W_f32"], g["col_scale"]).astype(np.float64)
+    opt = np.array([exact.lp_optimum(b, N)[0] for b in exact.blocks(imp, M)])
+
+    def arm(iters, greedy_only):
+        kw = dict(local_search_steps=0, flags=binding.TSENOR_FLAG_STRICT_PAPER) if greedy_only else {}
+        res = binding.solve(W, N, M, w.tau, iters, col_scale=cs, tau_mode=w.tau_mode, **kw)
+        torch.cuda.synchronize()
+        mask = res["mask"].cpu().numpy()
+        if not greedy_only:
+            assert exact.is_transposable_nm(mask, N, M)
+        return _relative_errors(mask, imp, opt, M, feasible=not greedy_only).mean()
+
+    print(f"[case] ablation arms {N}:{M}, {len(opt)} blocks", flush=True)
+    entropy_optround = arm(300, False)      # the method
+    entropy_greedy = arm(300, True)         # "Entropy + Greedy"
+    direct_optround = arm(0, False)         # Algorithm 2 on the importance itself
+    direct_greedy = arm(0, True)            # greedy selection on the importance itself
+    print(f"  mean relative error: entropy+optround {entropy_optround:.5f}, entropy+greedy {entropy_greedy:.5f}, "
+          f"optround {direct_optround:.5f}, greedy {direct_greedy:.5f}", flush=True)
+    # local search improves on greedy selection, with and without the entropy solution (App. B.2.1)
+    assert entropy_optround < entropy_greedy
+    assert direct_optround < direct_greedy
+    # rounding the entropy solution beats rounding the importance directly (Sec. 3.3 (i), App. B.2.1)
+    assert entropy_optround < direct_optround
+    # the full method is close to optimal on these inputs
+    assert entropy_optround < 0.01
+
+
+def test_a_converged_plan_rounds_better(dev):
+    # the error as a function of the iteration budget: a plan far from convergence (10 iterations) rounds
+    # worse than the importance itself, a converged one (1000) much better than either
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    N, M = 8, 16
+    w = synth.Workload("quality_iters", 8 * M, 16 * M, N, M, 0.005, 0, "f32", "normal", 3200)
+    g = synth.generate(w)
+    W = torch.from_numpy(g["W_store"]).to(dev)
+    imp = oracle.importance(g["W_f32"], None).astype(np.float64)
+    opt = np.array([exact.lp_optimum(b, N)[0] for b in exact.blocks(imp, M)])
+    errs = []
+    for iters in (0, 10, 100, 1000):
+        res = binding.solve(W, N, M, w.tau, iters, tau_mode=w.tau_mode)
+        torch.cuda.synchronize()
+        errs.append(_relative_errors(res["mask"].cpu().numpy(), imp, opt, M).mean())
+    print(f"[case] mean relative error after 0/10/100/1000 iterations: {errs}", flush=True)
+    assert errs[3] < errs[2] < errs[1]
+    assert errs[3] < 0.5 * errs[0]
