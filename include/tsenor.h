@@ -78,7 +78,14 @@ enum {
    * double-precision evaluation to ~1e-5 instead of ~1e-13, and the greedy order - hence the mask - can
    * differ from it in a block where two plan entries are closer than that (none in 8192 blocks of the
    * 16:32 test workload).  Sort keys, swap scores and all results stay in double.  Off by default. */
-  TSENOR_FLAG_FP32_ITERATIONS = 1u << 2
+  TSENOR_FLAG_FP32_ITERATIONS = 1u << 2,
+  /* Which kernel runs the greedy selection (Algorithm 2 lines 1-6).  Both give the same mask.  One takes
+   * one lane per block (fewest instructions: best when tens of thousands of blocks fill the chip), the other
+   * M lanes per block and decides M scan entries per step (shortest dependent chain: best for the small
+   * calls of a column-by-column pruning loop).  Default: chosen by the number of blocks in the launch.
+   * Setting both is an error. */
+  TSENOR_FLAG_GREEDY_ONE_LANE = 1u << 3,
+  TSENOR_FLAG_GREEDY_M_LANES = 1u << 4
 };
 
 typedef struct tsenor_problem {

@@ -109,6 +109,84 @@ __global__ __launch_bounds__(kWave) void greedy_kernel(Batch batch) {
   if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
 }
 
+// The same selection with M lanes per block: the block's scan order is taken M entries at a time, one entry
+// per lane, and all M are decided together.  An entry is rejected for certain when the entries before it in
+// the chunk that are already accepted fill its row or its column, and accepted for certain when its row and
+// its column have room even if every undecided entry before it were accepted; what is left undecided waits
+// for the next round.  The earliest undecided entry of a block always resolves, so the rounds end, and by
+// induction along the scan order every decision equals the sequential one.  Dependent chain: M chunks of a
+// few rounds instead of M*M steps.
+template <int M>
+__global__ __launch_bounds__(kWave) void greedy_wide_kernel(Batch batch) {
+  using mask_t = block_mask_t<M>;
+  constexpr int MM = M * M, G = kWave / M;
+  constexpr int LOGM = M == 4 ? 2 : M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
+  __shared__ mask_t rowbits[G][M];
+  __shared__ unsigned int colcnt[G][M];
+  const int which = find_problem(batch, blockIdx.x);
+  const unsigned short* order = batch.e[which].order;
+  const int64_t nblocks = batch.e[which].p.nblocks;
+  const int N = batch.e[which].p.N;
+  mask_t* rowmask = static_cast<mask_t*>(batch.e[which].rowmask);
+  WsHeader* hdr = batch.e[which].hdr;
+  const int lane = threadIdx.x, g = lane / M, ql = lane % M;
+  int64_t blk = (int64_t)(blockIdx.x - batch.first[which]) * G + g;
+  const bool active = blk < nblocks;
+  if (!active) blk = nblocks - 1;  // idle groups shadow the last block and write nothing
+  rowbits[g][ql] = 0;
+  colcnt[g][ql] = 0;
+  __syncthreads();
+  const unsigned long long gmask = (M == 64 ? ~0ull : ((1ull << M) - 1)) << (g * M);
+  const unsigned long long earlier = gmask & ((1ull << lane) - 1);  // lanes of this block before this one
+  const unsigned short* src = order + blk * MM + ql;
+  const int need = N * M;
+  int placed = 0;
+  unsigned int ahead = src[0];
+  for (int ch = 0; ch < M; ++ch) {
+    const unsigned int idx = ahead & (unsigned)(MM - 1);
+    if (ch + 1 < M) ahead = src[(ch + 1) * M];
+    const unsigned int i = idx / M, j = idx % M;
+    // lanes of this block whose entry lies in the same row / the same column
+    unsigned long long same_row = gmask, same_col = gmask;
+#pragma unroll
+    for (int b = 0; b < LOGM; ++b) {
+      const bool ib = (i >> b) & 1, jb = (j >> b) & 1;
+      const unsigned long long rows_b = __ballot(ib), cols_b = __ballot(jb);
+      same_row &= ib ? rows_b : ~rows_b;
+      same_col &= jb ? cols_b : ~cols_b;
+    }
+    const unsigned long long before_row = same_row & earlier, before_col = same_col & earlier;
+    const int room_row = N - mask_popc(rowbits[g][i]), room_col = N - (int)colcnt[g][j];
+    bool undecided = room_row > 0 && room_col > 0, take = false;
+    unsigned long long taken = 0, open = __ballot(undecided);
+    while (open) {
+      if (undecided) {
+        const int t_row = __popcll(taken & before_row), t_col = __popcll(taken & before_col);
+        const int o_row = __popcll(open & before_row), o_col = __popcll(open & before_col);
+        if (t_row >= room_row || t_col >= room_col) {
+          undecided = false;
+        } else if (t_row + o_row < room_row && t_col + o_col < room_col) {
+          undecided = false;
+          take = true;
+        }
+      }
+      taken = __ballot(take);
+      open = __ballot(undecided);
+    }
+    if (take) {
+      atomicOr(&rowbits[g][i], (mask_t)1 << j);
+      atomicAdd(&colcnt[g][j], 1u);
+    }
+    placed += __popcll(taken & gmask);
+    __syncthreads();
+    if (!__any(placed < need)) break;  // every block of the wave is full
+  }
+  if (active) rowmask[blk * M + ql] = rowbits[g][ql];
+  int missing = (active && ql == 0) ? need - placed : 0;
+  for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
+  if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
+}
+
 // Transpose of an M x M bit matrix held as one M-bit row per lane (M consecutive lanes): afterwards the
 // lane that held row r holds column r.  log2(M) block-swap steps.
 template <int M, int S = M / 2, class mask_t>

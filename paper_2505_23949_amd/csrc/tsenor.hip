@@ -130,7 +130,10 @@ int validate(const tsenor_problem* p) {
   if (p->M != 4 && p->M != 8 && p->M != 16 && p->M != 32 && p->M != 64) return TSENOR_ERR_UNSUPPORTED;
   if (p->dtype != TSENOR_F32 && p->dtype != TSENOR_BF16) return TSENOR_ERR_UNSUPPORTED;
   if (p->tau_mode != TSENOR_TAU_ABSOLUTE && p->tau_mode != TSENOR_TAU_REL_MATRIX_MAX) return TSENOR_ERR_UNSUPPORTED;
-  if (p->flags & ~(uint32_t)(TSENOR_FLAG_STRICT_PAPER | TSENOR_FLAG_COLS_FIRST | TSENOR_FLAG_FP32_ITERATIONS)) return TSENOR_ERR_UNSUPPORTED;
+  if (p->flags & ~(uint32_t)(TSENOR_FLAG_STRICT_PAPER | TSENOR_FLAG_COLS_FIRST | TSENOR_FLAG_FP32_ITERATIONS |
+                             TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES))
+    return TSENOR_ERR_UNSUPPORTED;
+  if ((p->flags & TSENOR_FLAG_GREEDY_ONE_LANE) && (p->flags & TSENOR_FLAG_GREEDY_M_LANES)) return TSENOR_ERR_PARAM;
   if (p->rows <= 0 || p->cols <= 0 || p->rows % p->M || p->cols % p->M || p->ld < p->cols) return TSENOR_ERR_SHAPE;
   if (p->rows > (int64_t)1 << 31 || p->cols > (int64_t)1 << 31 || p->rows * p->cols > (int64_t)1 << 40)
     return TSENOR_ERR_SHAPE;
@@ -150,11 +153,22 @@ inline bool degenerate(const tsenor_problem& p) { return p.N == 0 || p.N == p.M;
 struct Variant {
   int M;
   bool fast, zero_t;
-  bool operator==(const Variant& o) const { return M == o.M && fast == o.fast && zero_t == o.zero_t; }
+  uint32_t greedy;  // 0: chosen by size, else the TSENOR_FLAG_GREEDY_* asked for
+  bool operator==(const Variant& o) const {
+    return M == o.M && fast == o.fast && zero_t == o.zero_t && greedy == o.greedy;
+  }
 };
 inline Variant variant_of(const tsenor_problem& p) {
-  return {p.M, p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0, p.iters == 0};
+  return {p.M, p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0, p.iters == 0,
+          p.flags & (uint32_t)(TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES)};
 }
+
+// Below this many blocks in a launch the greedy selection runs with M lanes per block: the one-lane kernel
+// takes the time of M*M dependent steps of a single wave however few blocks there are (22 / 70 / 300 us for
+// M = 16 / 32 / 64), the M-lane kernel issues several times the instructions but its chain is M steps
+// (14 / 23 / 41 us), so it wins while it does not fill the chip.  Measured crossovers; for M <= 8 the
+// one-lane kernel is never slower.
+constexpr int64_t greedy_wide_below_blocks(int M) { return M == 16 ? 2500 : M == 32 ? 7000 : M == 64 ? 16000 : 0; }
 
 BatchEntry entry_of(const tsenor_problem& p, char* ws) {
   const WsLayout l = layout_of(p);
@@ -257,8 +271,16 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
       dykstra_sort_kernel<M, false><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
   }
   mark(2);
-  if (!assign_groups(b, blocks, kWave)) return TSENOR_ERR_SHAPE;
-  greedy_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
+  int64_t total_blocks = 0;
+  for (int k = 0; k < b.count; ++k) total_blocks += b.e[k].p.nblocks;
+  const bool wide = v.greedy ? v.greedy == TSENOR_FLAG_GREEDY_M_LANES : total_blocks < greedy_wide_below_blocks(M);
+  if (wide) {
+    if (!assign_groups(b, blocks, kWave / M)) return TSENOR_ERR_SHAPE;
+    greedy_wide_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
+  } else {
+    if (!assign_groups(b, blocks, kWave)) return TSENOR_ERR_SHAPE;
+    greedy_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
+  }
   mark(3);
   if (!assign_groups(b, blocks, kWave / M)) return TSENOR_ERR_SHAPE;
   finalize_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
@@ -430,7 +452,7 @@ const char* tsenor_status_string(int status) {
     case TSENOR_ERR_SHAPE: return "rows/cols must be positive multiples of M, ld >= cols, at most 2^40 weights";
     case TSENOR_ERR_NM: return "N must satisfy 0 <= N <= M";
     case TSENOR_ERR_UNSUPPORTED: return "unsupported M (4, 8, 16, 32, 64), dtype, tau_mode or flag";
-    case TSENOR_ERR_PARAM: return "tau must be finite and > 0 (>= 1/690 in REL_MATRIX_MAX mode), iters and local_search_steps >= 0";
+    case TSENOR_ERR_PARAM: return "tau must be finite and > 0 (>= 1/690 in REL_MATRIX_MAX mode), iters and local_search_steps >= 0, at most one TSENOR_FLAG_GREEDY_* flag";
     case TSENOR_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or smaller than tsenor_workspace_bytes";
     case TSENOR_ERR_HIP: return "a HIP call failed";
   }

@@ -132,6 +132,38 @@ def test_parity_cols_first_and_strict(dev, M, N):
     _check(base, g, got, ref, feasible=False)
 
 
+@pytest.mark.parametrize("M,N", [(4, 2), (8, 3), (16, 8), (32, 16), (32, 5), (64, 32)])
+def test_both_greedy_kernels_give_the_sequential_selection(dev, M, N):
+    # greedy selection only (strict mode, L = 0), so the mask IS the greedy kernel's output; inputs with many
+    # exact ties (values rounded to a few levels) make chunks in which one row or column occurs many times
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    rng = np.random.Generator(np.random.Philox(5000 + M + N))
+    rows, cols = 5 * M, 7 * M
+    for levels, iters in ((0, 40), (3, 0), (1, 0)):
+        Wf = rng.standard_normal((rows, cols)).astype(np.float32)
+        if levels:
+            Wf = np.round(Wf * levels) / np.float32(levels)
+        W = torch.from_numpy(Wf).to(dev)
+        ref = oracle.mask(Wf, N, M, 0.01, iters, tau_mode=oracle.TAU_REL_MATRIX_MAX, L=0, strict_paper=True)
+        full = oracle.mask(Wf, N, M, 0.01, iters, tau_mode=oracle.TAU_REL_MATRIX_MAX)
+        for name, flag in (("one lane", binding.TSENOR_FLAG_GREEDY_ONE_LANE),
+                           ("M lanes", binding.TSENOR_FLAG_GREEDY_M_LANES)):
+            print(f"[case] greedy kernel '{name}' {N}:{M} levels={levels} T={iters}", flush=True)
+            res = binding.solve(W, N, M, 0.01, iters, tau_mode=binding.TSENOR_TAU_REL_MATRIX_MAX,
+                                local_search_steps=0, flags=flag | binding.TSENOR_FLAG_STRICT_PAPER, want_stats=True)
+            torch.cuda.synchronize()
+            assert np.array_equal(res["mask"].cpu().numpy(), ref["mask"]), (name, levels)
+            assert np.array_equal(res["stats"].cpu().numpy(), ref["stats"]), (name, levels)
+            res = binding.solve(W, N, M, 0.01, iters, tau_mode=binding.TSENOR_TAU_REL_MATRIX_MAX, flags=flag,
+                                want_stats=True)
+            torch.cuda.synchronize()
+            assert np.array_equal(res["mask"].cpu().numpy(), full["mask"]), (name, levels)
+            assert np.array_equal(res["stats"].cpu().numpy(), full["stats"]), (name, levels)
+
+
 def test_zero_iterations_rounds_the_importance(dev):
     from dataclasses import replace
 
