@@ -164,6 +164,70 @@ def test_both_greedy_kernels_give_the_sequential_selection(dev, M, N):
             assert np.array_equal(res["stats"].cpu().numpy(), full["stats"]), (name, levels)
 
 
+def test_randomised_configurations(dev):
+    # 48 seeded draws over block size, N, shape, storage type, leading dimension, importance transforms, tau mode,
+    # iteration count and flags; the default-precision path must reproduce the oracle's mask and counters exactly
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    rng = np.random.Generator(np.random.Philox(777))
+    for case in range(48):
+        M = int(rng.choice([4, 8, 16, 32, 64]))
+        N = int(rng.integers(1, M))
+        rows, cols = M * int(rng.integers(1, 6)), M * int(rng.integers(1, 7))
+        bf16 = bool(rng.integers(0, 2))
+        pad = int(rng.choice([0, 8, 24]))
+        use_cs, use_add, square = (bool(rng.integers(0, 2)) for _ in range(3))
+        rel = bool(rng.integers(0, 3))
+        iters = int(rng.choice([0, 1, 7, 30, 120]))
+        strict, cols_first = bool(rng.integers(0, 4) == 0), bool(rng.integers(0, 2))
+        L = int(rng.choice([0, 1, 10]))
+        greedy = int(rng.choice([0, binding.TSENOR_FLAG_GREEDY_ONE_LANE, binding.TSENOR_FLAG_GREEDY_M_LANES]))
+        dist = rng.choice(["normal", "student_t", "few_levels"])
+        if dist == "normal":
+            Wf = (0.02 * rng.standard_normal((rows, cols))).astype(np.float32)
+        elif dist == "student_t":
+            Wf = (0.02 * rng.standard_t(3, (rows, cols))).astype(np.float32)
+        else:
+            # exact ties in the importance: only without iterations, where both sides order them by index; after
+            # an iteration equal entries become ties up to rounding, which no two implementations break alike
+            Wf = (rng.integers(-3, 4, (rows, cols)) * 0.25).astype(np.float32)
+            iters, use_add, use_cs = 0, False, False
+        Vf = (0.01 * rng.standard_normal((rows, cols))).astype(np.float32)
+        cs = rng.lognormal(0.0, 1.0, cols).astype(np.float32) if use_cs else None
+        tdt = torch.bfloat16 if bf16 else torch.float32
+        big = torch.zeros((rows, cols + pad), dtype=tdt, device=dev)
+        big[:, :cols] = torch.from_numpy(Wf).to(dev).to(tdt)
+        W = big[:, :cols]
+        Wf = W.float().cpu().numpy()
+        add = None
+        if use_add:
+            bigv = torch.zeros((rows, cols + pad), dtype=tdt, device=dev)
+            bigv[:, :cols] = torch.from_numpy(Vf).to(dev).to(tdt)
+            add = bigv[:, :cols]
+            Vf = add.float().cpu().numpy()
+        csd = None if cs is None else torch.from_numpy(cs).to(dev)
+        tau = 0.01 if rel else 30.0
+        flags = (binding.TSENOR_FLAG_STRICT_PAPER if strict else 0) | \
+                (binding.TSENOR_FLAG_COLS_FIRST if cols_first else 0) | greedy
+        desc = (f"case {case}: {N}:{M} {rows}x{cols}+{pad} bf16={bf16} cs={use_cs} add={use_add} sq={square} rel={rel} "
+                f"T={iters} strict={strict} L={L} cols_first={cols_first} greedy={greedy} {dist}")
+        print(f"[case] {desc}", flush=True)
+        res = binding.solve(W, N, M, tau, iters, col_scale=csd, tau_mode=int(rel), local_search_steps=L, flags=flags,
+                            add=add, add_scale=0.5, want_plan=True, want_stats=True,
+                            importance=binding.TSENOR_IMPORTANCE_SQUARE if square else binding.TSENOR_IMPORTANCE_ABS)
+        torch.cuda.synchronize()
+        ref = oracle.solve_ex(Wf, N, M, tau, iters, add=Vf if use_add else None, add_scale=0.5, col_scale=cs,
+                              square=square, tau_mode=int(rel), L=L, strict_paper=strict, cols_first=cols_first)
+        S_ref = np.exp(ref["log_S"])
+        plan = res["plan"].cpu().numpy()
+        err = np.abs(plan / S_ref - 1.0).max() if iters == 0 else np.abs(plan - S_ref).max()
+        assert err <= PLAN_ATOL, (desc, err)
+        assert np.array_equal(res["mask"].cpu().numpy(), ref["mask"]), desc
+        assert np.array_equal(res["stats"].cpu().numpy(), ref["stats"]), desc
+
+
 def test_zero_iterations_rounds_the_importance(dev):
     from dataclasses import replace
 
