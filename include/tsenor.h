@@ -85,7 +85,15 @@ enum {
    * calls of a column-by-column pruning loop).  Default: chosen by the number of blocks in the launch.
    * Setting both is an error. */
   TSENOR_FLAG_GREEDY_ONE_LANE = 1u << 3,
-  TSENOR_FLAG_GREEDY_M_LANES = 1u << 4
+  TSENOR_FLAG_GREEDY_M_LANES = 1u << 4,
+  /* How the Dykstra kernel spreads a block over lanes.  Same arithmetic, same results up to the order of
+   * the additions inside a row or column sum (~1e-15).  LARGE tiles: 32 entries per lane (fewest
+   * instructions per entry: best for full matrices).  SMALL tiles (M = 16 and 32 only, double-precision
+   * iterations with iters > 0; ignored otherwise): 16 entries per lane, twice the lanes per block, a
+   * shorter dependent chain per iteration: best while the launch cannot fill the chip anyway.  Default:
+   * chosen by the number of blocks in the launch.  Setting both is an error. */
+  TSENOR_FLAG_TILES_LARGE = 1u << 5,
+  TSENOR_FLAG_TILES_SMALL = 1u << 6
 };
 
 typedef struct tsenor_problem {

@@ -34,6 +34,8 @@ TSENOR_FLAG_COLS_FIRST = 1 << 1
 TSENOR_FLAG_FP32_ITERATIONS = 1 << 2
 TSENOR_FLAG_GREEDY_ONE_LANE = 1 << 3
 TSENOR_FLAG_GREEDY_M_LANES = 1 << 4
+TSENOR_FLAG_TILES_LARGE = 1 << 5
+TSENOR_FLAG_TILES_SMALL = 1 << 6
 TSENOR_IMPORTANCE_ABS = 0
 TSENOR_IMPORTANCE_SQUARE = 1
 

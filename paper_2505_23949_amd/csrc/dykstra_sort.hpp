@@ -50,38 +50,60 @@ constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 // Per-M tiling.  XM[s] / YM[s]: lane masks of the exchange steps along a lane-row / lane-column.
 // The top bit of XM[s] is lane bit NX-1-s (mirror masks keep the exchanges on DPP); YM[s] is a single
 // lane bit, listed cheapest mechanism first because the first step moves the most registers.
-template <int M>
+// SMALL: a finer tiling (more lanes per block, fewer entries per lane) for launches that cannot fill the
+// chip anyway: the dependent chain of an iteration is shorter.  Where a tile has fewer rows than the
+// lane-row has lanes, the last exchange steps of a reduction have no registers left to split: they add the
+// partner's value into the same register instead (both lanes end up owning the same sum).
+template <int M, bool SMALL = false>
 struct Tiling;
 template <>
-struct Tiling<4> {
+struct Tiling<4, false> {
   static constexpr int NX = 0, NY = 0;
   static constexpr int XM[1] = {1}, YM[1] = {1};
   static constexpr bool STORE_E = true;
 };
 template <>
-struct Tiling<8> {
+struct Tiling<8, false> {
   static constexpr int NX = 1, NY = 1;
   static constexpr int XM[1] = {1}, YM[1] = {2};
   static constexpr bool STORE_E = true;
 };
 template <>
-struct Tiling<16> {
+struct Tiling<16, false> {
   static constexpr int NX = 2, NY = 1;  // 8 lanes per block, 8 x 4 tiles
   static constexpr int XM[2] = {3, 1}, YM[1] = {4};
   static constexpr bool STORE_E = true;
 };
 template <>
-struct Tiling<32> {
+struct Tiling<32, false> {
   static constexpr int NX = 3, NY = 2;  // 32 lanes per block, 8 x 4 tiles
   static constexpr int XM[3] = {7, 3, 1}, YM[2] = {8, 16};
   static constexpr bool STORE_E = true;
 };
 template <>
-struct Tiling<64> {
+struct Tiling<64, false> {
   static constexpr int NX = 3, NY = 3;  // 64 lanes per block, 8 x 8 tiles; too large to hold e as doubles
   static constexpr int XM[3] = {7, 3, 1}, YM[3] = {8, 16, 32};
   static constexpr bool STORE_E = false;
 };
+template <>
+struct Tiling<16, true> {
+  static constexpr int NX = 2, NY = 2;  // 16 lanes per block, 4 x 4 tiles
+  static constexpr int XM[2] = {3, 1}, YM[2] = {8, 4};
+  static constexpr bool STORE_E = true;
+};
+template <>
+struct Tiling<32, true> {
+  static constexpr int NX = 3, NY = 3;  // 64 lanes per block, 4 x 4 tiles
+  static constexpr int XM[3] = {7, 3, 1}, YM[3] = {8, 16, 32};
+  static constexpr bool STORE_E = true;
+};
+
+// registers a lane owns after a reduce-scatter of `count` values over 2^steps lanes (at least one)
+constexpr int owned(int count, int steps) { return (count >> steps) > 0 ? (count >> steps) : 1; }
+// lane coordinate -> register offset of the row mapping: the top log2(TH) bits of gx if the tile has fewer
+// rows than the lane-row has lanes, gx shifted up otherwise
+constexpr int shift_lane(int x, int sh) { return sh >= 0 ? x << sh : x >> -sh; }
 
 // 1/d from the hardware estimate x0 (~24 bits for double).  With e = 1 - d x0, 1/d = x0 (1 + e + e^2 + ...):
 // the terms up to e^2 leave an error of e^3 ~ 2^-72, in three fused operations.  One Newton step for float.
@@ -103,15 +125,19 @@ __device__ __forceinline__ double vfma(double a, double b, double c) { return fm
 __device__ __forceinline__ float vfma(float a, float b, float c) { return fmaf(a, b, c); }
 
 // Recursive halving over the lanes of a lane-row.  v[0..TH): partial sums, register a <-> tile row
-// a ^ (gx << SH).  Afterwards v[0 .. TH >> NX) hold complete sums.
+// a ^ shift_lane(gx, SH).  Afterwards v[0 .. owned(TH, NX)) hold complete sums.
 template <class T, class real, int TH, int S = 0>
 __device__ __forceinline__ void reduce_scatter_x(real (&v)[TH]) {
   if constexpr (S < T::NX) {
     constexpr int SH = ilog2(TH) - T::NX;
     constexpr int h = TH >> (S + 1);
-    constexpr int am = (T::XM[S] << SH) & (2 * h - 1);  // register index of the partner's matching value
+    if constexpr (h >= 1) {
+      constexpr int am = shift_lane(T::XM[S], SH) & (2 * h - 1);  // register index of the partner's matching value
 #pragma unroll
-    for (int a = 0; a < h; ++a) v[a] += lane_xor<T::XM[S]>(v[a ^ am]);
+      for (int a = 0; a < h; ++a) v[a] += lane_xor<T::XM[S]>(v[a ^ am]);
+    } else {
+      v[0] += lane_xor<T::XM[S]>(v[0]);  // no registers left to split: both lanes keep the sum
+    }
     reduce_scatter_x<T, real, TH, S + 1>(v);
   }
 }
@@ -120,9 +146,11 @@ __device__ __forceinline__ void all_gather_x(real (&v)[TH]) {
   if constexpr (S >= 0) {
     constexpr int SH = ilog2(TH) - T::NX;
     constexpr int h = TH >> (S + 1);
-    constexpr int am = (T::XM[S] << SH) & (2 * h - 1);
+    if constexpr (h >= 1) {
+      constexpr int am = shift_lane(T::XM[S], SH) & (2 * h - 1);
 #pragma unroll
-    for (int a = 0; a < h; ++a) v[a ^ am] = lane_xor<T::XM[S]>(v[a]);
+      for (int a = 0; a < h; ++a) v[a ^ am] = lane_xor<T::XM[S]>(v[a]);
+    }
     all_gather_x<T, real, TH, S - 1>(v);
   }
 }
@@ -131,8 +159,12 @@ template <class T, class real, int TW, int S = 0>
 __device__ __forceinline__ void reduce_scatter_y(real (&v)[TW]) {
   if constexpr (S < T::NY) {
     constexpr int h = TW >> (S + 1);
+    if constexpr (h >= 1) {
 #pragma unroll
-    for (int b = 0; b < h; ++b) v[b] += lane_xor<T::YM[S]>(v[b + h]);
+      for (int b = 0; b < h; ++b) v[b] += lane_xor<T::YM[S]>(v[b + h]);
+    } else {
+      v[0] += lane_xor<T::YM[S]>(v[0]);
+    }
     reduce_scatter_y<T, real, TW, S + 1>(v);
   }
 }
@@ -140,8 +172,10 @@ template <class T, class real, int TW, int S = T::NY - 1>
 __device__ __forceinline__ void all_gather_y(real (&v)[TW]) {
   if constexpr (S >= 0) {
     constexpr int h = TW >> (S + 1);
+    if constexpr (h >= 1) {
 #pragma unroll
-    for (int b = 0; b < h; ++b) v[b + h] = lane_xor<T::YM[S]>(v[b]);
+      for (int b = 0; b < h; ++b) v[b + h] = lane_xor<T::YM[S]>(v[b]);
+    }
     all_gather_y<T, real, TW, S - 1>(v);
   }
 }
@@ -161,7 +195,7 @@ __device__ __forceinline__ int reg_xor_y(int q) {
 template <class T, bool STORE, class real, int TH, int TW>
 __device__ __forceinline__ void dykstra_iteration(const real (&kap)[TH][TW], real (&U)[TH], real (&V)[TW], real Nd,
                                                   real floor_) {
-  constexpr int OWN_R = TH >> T::NX, OWN_C = TW >> T::NY;
+  constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
   real e[STORE ? TH : 1][STORE ? TW : 1];
   real R[TH], C[TW];
   // projection onto C1 (line 3) of the plan capped by the previous iteration
@@ -221,7 +255,7 @@ __device__ __forceinline__ void dykstra_iteration(const real (&kap)[TH][TW], rea
 template <class T, int TH, int TW>
 __device__ __forceinline__ void dykstra_iteration_f32(const float (&kap)[TH][TW], float (&U)[TH], float (&Uinv)[TH],
                                                       float (&V)[TW], float Nf) {
-  constexpr int OWN_R = TH >> T::NX, OWN_C = TW >> T::NY;
+  constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
   float e[TH][TW], S[TH], C[TW];
 #pragma unroll
   for (int a = 0; a < TH; ++a) {
@@ -326,10 +360,10 @@ struct DykstraLaunch {
 
 // ZERO_T: the instantiation for T = 0 (no iterations, keys are K itself).  It is a template parameter
 // rather than a branch because keeping both paths in one kernel costs the iterating path ~40 registers.
-template <int M, bool FAST, bool ZERO_T = false>
+template <int M, bool FAST, bool ZERO_T = false, bool SMALL = false>
 __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<M, FAST>::kWavesPerSimd)) void dykstra_sort_kernel(
     Batch batch) {
-  using T = Tiling<M>;
+  using T = Tiling<M, SMALL>;
   const int which = find_problem(batch, blockIdx.x);
   const DevProblem p = batch.e[which].p;
   const WsHeader* hdr = batch.e[which].hdr;
@@ -339,7 +373,6 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
   const unsigned int group = blockIdx.x - batch.first[which];  // workgroup index within the matrix
   constexpr int GX = 1 << T::NX, GY = 1 << T::NY, TH = M / GY, TW = M / GX, LPB = GX * GY, BPW = kWave / LPB,
                 E = TH * TW, SHX = ilog2(TH) - T::NX, WPG = DykstraLaunch<M, FAST>::kWavesPerGroup;
-  static_assert(TH >= GX && TW >= GY, "every lane must end a reduce-scatter with at least one sum");
   const int lane = threadIdx.x & (kWave - 1), wave_in_group = threadIdx.x / kWave;
   const int64_t wave = (int64_t)group * WPG + wave_in_group;
   const int q = lane % LPB, gx = q % GX, gy = q / GX;
@@ -353,7 +386,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
   // register (a, b) of this lane <-> in-kernel coordinates (ri, cj) of the block.  Each phase of the
   // kernel takes its own opaque copy of the lane offsets, so that element addresses are recomputed where
   // they are needed instead of being kept in registers across the iteration loop.
-  const int rx = gx << SHX, ry = reg_xor_y<T, TW>(q);
+  const int rx = shift_lane(gx, SHX), ry = reg_xor_y<T, TW>(q);
   auto fresh = [](int v) {
     asm volatile("" : "+v"(v));
     return v;
@@ -424,7 +457,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
     const double Nd = (double)p.N;
     // logs of the scalings of the rows and columns this lane owns (the first registers after a
     // reduce-scatter); the other lanes of the lane-row / lane-column hold the same values for theirs
-    constexpr int OWN_R = TH >> T::NX, OWN_C = TW >> T::NY;
+    constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
     double lu_own[OWN_R], lv_own[OWN_C];
     {
       double U[TH], V[TW];

@@ -131,9 +131,11 @@ int validate(const tsenor_problem* p) {
   if (p->dtype != TSENOR_F32 && p->dtype != TSENOR_BF16) return TSENOR_ERR_UNSUPPORTED;
   if (p->tau_mode != TSENOR_TAU_ABSOLUTE && p->tau_mode != TSENOR_TAU_REL_MATRIX_MAX) return TSENOR_ERR_UNSUPPORTED;
   if (p->flags & ~(uint32_t)(TSENOR_FLAG_STRICT_PAPER | TSENOR_FLAG_COLS_FIRST | TSENOR_FLAG_FP32_ITERATIONS |
-                             TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES))
+                             TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES | TSENOR_FLAG_TILES_LARGE |
+                             TSENOR_FLAG_TILES_SMALL))
     return TSENOR_ERR_UNSUPPORTED;
   if ((p->flags & TSENOR_FLAG_GREEDY_ONE_LANE) && (p->flags & TSENOR_FLAG_GREEDY_M_LANES)) return TSENOR_ERR_PARAM;
+  if ((p->flags & TSENOR_FLAG_TILES_LARGE) && (p->flags & TSENOR_FLAG_TILES_SMALL)) return TSENOR_ERR_PARAM;
   if (p->rows <= 0 || p->cols <= 0 || p->rows % p->M || p->cols % p->M || p->ld < p->cols) return TSENOR_ERR_SHAPE;
   if (p->rows > (int64_t)1 << 31 || p->cols > (int64_t)1 << 31 || p->rows * p->cols > (int64_t)1 << 40)
     return TSENOR_ERR_SHAPE;
@@ -154,14 +156,22 @@ struct Variant {
   int M;
   bool fast, zero_t;
   uint32_t greedy;  // 0: chosen by size, else the TSENOR_FLAG_GREEDY_* asked for
+  uint32_t tiles;   // 0: chosen by size, else the TSENOR_FLAG_TILES_* asked for
   bool operator==(const Variant& o) const {
-    return M == o.M && fast == o.fast && zero_t == o.zero_t && greedy == o.greedy;
+    return M == o.M && fast == o.fast && zero_t == o.zero_t && greedy == o.greedy && tiles == o.tiles;
   }
 };
 inline Variant variant_of(const tsenor_problem& p) {
   return {p.M, p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0, p.iters == 0,
-          p.flags & (uint32_t)(TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES)};
+          p.flags & (uint32_t)(TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES),
+          p.flags & (uint32_t)(TSENOR_FLAG_TILES_LARGE | TSENOR_FLAG_TILES_SMALL)};
 }
+
+// Below this many blocks in a launch the Dykstra kernel uses the small tiles (M = 16 and 32, double
+// iterations): with so few waves every SIMD holds at most one, whose iteration time is its instruction count.
+// Measured crossovers (M = 32: 108 us against 140 us for the 300 iterations of a few blocks; M = 16: 91 us
+// against 146 us).
+constexpr int64_t small_tiles_below_blocks(int M) { return M == 16 ? 9000 : M == 32 ? 1500 : 0; }
 
 // Below this many blocks in a launch the greedy selection runs with M lanes per block: the one-lane kernel
 // takes the time of M*M dependent steps of a single wave however few blocks there are (22 / 70 / 300 us for
@@ -258,7 +268,19 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   mark(1);
   constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
   const auto blocks = [](const BatchEntry& e) { return e.p.nblocks; };
-  if (v.fast) {
+  int64_t total_blocks = 0;
+  for (int k = 0; k < b.count; ++k) total_blocks += b.e[k].p.nblocks;
+  constexpr bool kHasSmall = M == 16 || M == 32;
+  const bool small = kHasSmall && !v.fast && !v.zero_t &&
+                     (v.tiles ? v.tiles == TSENOR_FLAG_TILES_SMALL : total_blocks < small_tiles_below_blocks(M));
+  if (small) {
+    if constexpr (kHasSmall) {
+      using L = DykstraLaunch<M, false>;
+      constexpr int BPWS = kWave >> (Tiling<M, true>::NX + Tiling<M, true>::NY);
+      if (!assign_groups(b, blocks, (int64_t)BPWS * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
+      dykstra_sort_kernel<M, false, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
+    }
+  } else if (v.fast) {
     using L = DykstraLaunch<M, true>;
     if (!assign_groups(b, blocks, (int64_t)BPW * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
     dykstra_sort_kernel<M, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
@@ -271,8 +293,6 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
       dykstra_sort_kernel<M, false><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
   }
   mark(2);
-  int64_t total_blocks = 0;
-  for (int k = 0; k < b.count; ++k) total_blocks += b.e[k].p.nblocks;
   const bool wide = v.greedy ? v.greedy == TSENOR_FLAG_GREEDY_M_LANES : total_blocks < greedy_wide_below_blocks(M);
   if (wide) {
     if (!assign_groups(b, blocks, kWave / M)) return TSENOR_ERR_SHAPE;
@@ -452,7 +472,7 @@ const char* tsenor_status_string(int status) {
     case TSENOR_ERR_SHAPE: return "rows/cols must be positive multiples of M, ld >= cols, at most 2^40 weights";
     case TSENOR_ERR_NM: return "N must satisfy 0 <= N <= M";
     case TSENOR_ERR_UNSUPPORTED: return "unsupported M (4, 8, 16, 32, 64), dtype, tau_mode or flag";
-    case TSENOR_ERR_PARAM: return "tau must be finite and > 0 (>= 1/690 in REL_MATRIX_MAX mode), iters and local_search_steps >= 0, at most one TSENOR_FLAG_GREEDY_* flag";
+    case TSENOR_ERR_PARAM: return "tau must be finite and > 0 (>= 1/690 in REL_MATRIX_MAX mode), iters and local_search_steps >= 0, at most one TSENOR_FLAG_GREEDY_* and one TSENOR_FLAG_TILES_* flag";
     case TSENOR_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or smaller than tsenor_workspace_bytes";
     case TSENOR_ERR_HIP: return "a HIP call failed";
   }

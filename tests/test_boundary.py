@@ -174,6 +174,8 @@ def test_validation_of_the_extended_fields(lib):
     assert call(_problem(importance=2)) == b.TSENOR_ERR_UNSUPPORTED
     assert call(_problem(flags=b.TSENOR_FLAG_GREEDY_ONE_LANE | b.TSENOR_FLAG_GREEDY_M_LANES)) == b.TSENOR_ERR_PARAM
     assert call(_problem(flags=b.TSENOR_FLAG_GREEDY_M_LANES)) == b.TSENOR_ERR_WORKSPACE
+    assert call(_problem(flags=b.TSENOR_FLAG_TILES_LARGE | b.TSENOR_FLAG_TILES_SMALL)) == b.TSENOR_ERR_PARAM
+    assert call(_problem(flags=b.TSENOR_FLAG_TILES_SMALL)) == b.TSENOR_ERR_WORKSPACE
     assert call(_problem(add=0x3000, add_scale=float("inf"))) == b.TSENOR_ERR_PARAM
     assert call(_problem(add=0x3000, add_scale=0.5)) == b.TSENOR_ERR_WORKSPACE
     odd = dict(M=4, N=2, rows=8, cols=12, ld=12)

@@ -184,6 +184,7 @@ def test_randomised_configurations(dev):
         strict, cols_first = bool(rng.integers(0, 4) == 0), bool(rng.integers(0, 2))
         L = int(rng.choice([0, 1, 10]))
         greedy = int(rng.choice([0, binding.TSENOR_FLAG_GREEDY_ONE_LANE, binding.TSENOR_FLAG_GREEDY_M_LANES]))
+        greedy |= int(rng.choice([0, binding.TSENOR_FLAG_TILES_LARGE, binding.TSENOR_FLAG_TILES_SMALL]))
         dist = rng.choice(["normal", "student_t", "few_levels"])
         if dist == "normal":
             Wf = (0.02 * rng.standard_normal((rows, cols))).astype(np.float32)
@@ -226,6 +227,31 @@ def test_randomised_configurations(dev):
         assert err <= PLAN_ATOL, (desc, err)
         assert np.array_equal(res["mask"].cpu().numpy(), ref["mask"]), desc
         assert np.array_equal(res["stats"].cpu().numpy(), ref["stats"]), desc
+
+
+@pytest.mark.parametrize("M,N,dtype", [(16, 8, "f32"), (32, 16, "bf16"), (32, 7, "f32"), (16, 3, "bf16")])
+def test_both_tilings_of_the_dykstra_kernel(dev, M, N, dtype):
+    # ragged block counts for both tilings (M = 32: one block per wave / two; M = 16: four / eight)
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.Workload(f"tiles_{N}of{M}", 3 * M, 7 * M, N, M, 0.005, 150, dtype, "wanda", 6100 + M + N)
+    for cols_first in (False, True):
+        for name, flag in (("large", binding.TSENOR_FLAG_TILES_LARGE), ("small", binding.TSENOR_FLAG_TILES_SMALL)):
+            g = synth.generate(w)
+            W, cs = _to_device(g, w, dev)
+            flags = flag | (binding.TSENOR_FLAG_COLS_FIRST if cols_first else 0)
+            print(f"[case] {name} tiles {w.name} {dtype} cols_first={cols_first}", flush=True)
+            res = binding.solve(W, N, M, w.tau, w.iters, col_scale=cs, tau_mode=w.tau_mode, flags=flags,
+                                want_plan=True, want_stats=True)
+            torch.cuda.synchronize()
+            ref = oracle.mask(g["W_f32"], N, M, w.tau, w.iters, col_scale=g["col_scale"], tau_mode=w.tau_mode,
+                              cols_first=cols_first, return_plan=True)
+            got = {"mask": res["mask"].cpu().numpy(), "plan": res["plan"].cpu().numpy(),
+                   "stats": res["stats"].cpu().numpy(), "tau_eff": float(res["tau_eff"].cpu().numpy()[0])}
+            _check(w, g, got, ref)
+            assert np.array_equal(got["mask"], ref["mask"])
 
 
 def test_zero_iterations_rounds_the_importance(dev):
