@@ -102,7 +102,8 @@ def main() -> int:
     ap.add_argument("--cols", type=int, default=0, help="override cols (debug)")
     ap.add_argument("--iters", type=int, default=-1, help="override the iteration count T (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=1024)
+    ap.add_argument("--cpu-sample-rows", type=int, default=4096,
+                    help="rows of the matrix the CPU oracle is timed on (default: the whole headline matrix, ~10 s)")
     ap.add_argument("--fp32-iterations", action="store_true",
                     help="time the TSENOR_FLAG_FP32_ITERATIONS mode (iterations after the eighth in fp32)")
     ap.add_argument("--no-fp32-mode", action="store_true",
