@@ -93,7 +93,11 @@ enum {
    * shorter dependent chain per iteration: best while the launch cannot fill the chip anyway.  Default:
    * chosen by the number of blocks in the launch.  Setting both is an error. */
   TSENOR_FLAG_TILES_LARGE = 1u << 5,
-  TSENOR_FLAG_TILES_SMALL = 1u << 6
+  TSENOR_FLAG_TILES_SMALL = 1u << 6,
+  /* Ablation arm "Simple" of App. B.2.1 in place of Algorithm 2: per block, keep the N largest plan entries
+   * of every row, then of what is left the N largest of every column (ties to the lower index).  No local
+   * search: rows may keep fewer than N entries (stats_out[3] counts what is missing). */
+  TSENOR_FLAG_SIMPLE_ROUNDING = 1u << 7
 };
 
 typedef struct tsenor_problem {

@@ -178,6 +178,30 @@ def round_plan(key, imp, N: int, M: int, L: int = 10, strict_paper: bool = False
     return mask, stats
 
 
+def simple_round(key, N: int, M: int) -> np.ndarray:
+    """The "Simple" rounding arm of App. B.2.1, written out as its definition: in every block keep the N
+    largest entries of each row (row-wise N:M rounding of the plan), then, of what is left, the N largest of
+    each column.  Ties go to the lower index.  Rows may end up with fewer than N entries."""
+    key = np.ascontiguousarray(key, dtype=np.float64)
+    rows, cols = key.shape
+    out = np.zeros((rows, cols), dtype=np.uint8)
+    for r0 in range(0, rows, M):
+        for c0 in range(0, cols, M):
+            blk = key[r0:r0 + M, c0:c0 + M]
+            kept = np.zeros((M, M), dtype=bool)
+            for i in range(M):
+                order = sorted(range(M), key=lambda j: (-blk[i, j], j))
+                kept[i, order[:N]] = True
+            final = np.zeros((M, M), dtype=np.uint8)
+            for j in range(M):
+                cand = [i for i in range(M) if kept[i, j]]
+                cand.sort(key=lambda i: (-blk[i, j], i))
+                for i in cand[:N]:
+                    final[i, j] = 1
+            out[r0:r0 + M, c0:c0 + M] = final
+    return out
+
+
 def swap_scores(imp_block, S_block, i: int, j: int) -> np.ndarray:
     """Eq. (5) score matrix of one block for deficient row i and column j (0-based)."""
     imp_block = _f32(imp_block)

@@ -36,6 +36,7 @@ TSENOR_FLAG_GREEDY_ONE_LANE = 1 << 3
 TSENOR_FLAG_GREEDY_M_LANES = 1 << 4
 TSENOR_FLAG_TILES_LARGE = 1 << 5
 TSENOR_FLAG_TILES_SMALL = 1 << 6
+TSENOR_FLAG_SIMPLE_ROUNDING = 1 << 7
 TSENOR_IMPORTANCE_ABS = 0
 TSENOR_IMPORTANCE_SQUARE = 1
 

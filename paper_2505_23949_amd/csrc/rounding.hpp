@@ -109,6 +109,54 @@ __global__ __launch_bounds__(kWave) void greedy_kernel(Batch batch) {
   if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
 }
 
+// Ablation arm "Simple" (App. B.2.1): row-wise then column-wise N:M rounding of the plan.  In scan order
+// (descending plan, ties by index) an entry survives the row stage while its row has passed fewer than N
+// entries, and a survivor is kept while its column holds fewer than N: the first N of every row, then the
+// first N survivors of every column.  One lane per block, same output as greedy_kernel.
+template <int M>
+__global__ __launch_bounds__(kWave) void simple_round_kernel(Batch batch) {
+  using mask_t = block_mask_t<M>;
+  constexpr int MM = M * M;
+  __shared__ mask_t rowbits[M][kWave];
+  __shared__ unsigned char passed[M][kWave], colcnt[M][kWave];
+  const int which = find_problem(batch, blockIdx.x);
+  const unsigned short* order = batch.e[which].order;
+  const int64_t nblocks = batch.e[which].p.nblocks;
+  const int N = batch.e[which].p.N;
+  mask_t* rowmask = static_cast<mask_t*>(batch.e[which].rowmask);
+  WsHeader* hdr = batch.e[which].hdr;
+  const int lane = threadIdx.x;
+  const int64_t blk = (int64_t)(blockIdx.x - batch.first[which]) * kWave + lane;
+  for (int k = 0; k < M; ++k) {
+    rowbits[k][lane] = 0;
+    passed[k][lane] = 0;
+    colcnt[k][lane] = 0;
+  }
+  int missing = 0;
+  if (blk < nblocks) {
+    const unsigned short* src = order + blk * MM;
+    int placed = 0;
+    for (int h = 0; h < MM; ++h) {
+      const unsigned int idx = src[h] & (unsigned)(MM - 1);
+      const unsigned int i = idx / M, j = idx % M;
+      const unsigned int through = passed[i][lane];
+      if (through < (unsigned)N) {
+        passed[i][lane] = (unsigned char)(through + 1);
+        const unsigned int cj = colcnt[j][lane];
+        if (cj < (unsigned)N) {
+          colcnt[j][lane] = (unsigned char)(cj + 1);
+          rowbits[i][lane] |= (mask_t)1 << j;
+          ++placed;
+        }
+      }
+    }
+    for (int k = 0; k < M; ++k) rowmask[blk * M + k] = rowbits[k][lane];
+    missing = N * M - placed;
+  }
+  for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
+  if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
+}
+
 // The same selection with M lanes per block: the block's scan order is taken M entries at a time, one entry
 // per lane, and all M are decided together.  An entry is rejected for certain when the entries before it in
 // the chunk that are already accepted fill its row or its column, and accepted for certain when its row and

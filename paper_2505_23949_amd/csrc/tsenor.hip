@@ -132,7 +132,7 @@ int validate(const tsenor_problem* p) {
   if (p->tau_mode != TSENOR_TAU_ABSOLUTE && p->tau_mode != TSENOR_TAU_REL_MATRIX_MAX) return TSENOR_ERR_UNSUPPORTED;
   if (p->flags & ~(uint32_t)(TSENOR_FLAG_STRICT_PAPER | TSENOR_FLAG_COLS_FIRST | TSENOR_FLAG_FP32_ITERATIONS |
                              TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES | TSENOR_FLAG_TILES_LARGE |
-                             TSENOR_FLAG_TILES_SMALL))
+                             TSENOR_FLAG_TILES_SMALL | TSENOR_FLAG_SIMPLE_ROUNDING))
     return TSENOR_ERR_UNSUPPORTED;
   if ((p->flags & TSENOR_FLAG_GREEDY_ONE_LANE) && (p->flags & TSENOR_FLAG_GREEDY_M_LANES)) return TSENOR_ERR_PARAM;
   if ((p->flags & TSENOR_FLAG_TILES_LARGE) && (p->flags & TSENOR_FLAG_TILES_SMALL)) return TSENOR_ERR_PARAM;
@@ -157,14 +157,17 @@ struct Variant {
   bool fast, zero_t;
   uint32_t greedy;  // 0: chosen by size, else the TSENOR_FLAG_GREEDY_* asked for
   uint32_t tiles;   // 0: chosen by size, else the TSENOR_FLAG_TILES_* asked for
+  bool simple;      // TSENOR_FLAG_SIMPLE_ROUNDING
   bool operator==(const Variant& o) const {
-    return M == o.M && fast == o.fast && zero_t == o.zero_t && greedy == o.greedy && tiles == o.tiles;
+    return M == o.M && fast == o.fast && zero_t == o.zero_t && greedy == o.greedy && tiles == o.tiles &&
+           simple == o.simple;
   }
 };
 inline Variant variant_of(const tsenor_problem& p) {
   return {p.M, p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0, p.iters == 0,
           p.flags & (uint32_t)(TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES),
-          p.flags & (uint32_t)(TSENOR_FLAG_TILES_LARGE | TSENOR_FLAG_TILES_SMALL)};
+          p.flags & (uint32_t)(TSENOR_FLAG_TILES_LARGE | TSENOR_FLAG_TILES_SMALL),
+          (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0};
 }
 
 // Below this many blocks in a launch the Dykstra kernel uses the small tiles (M = 16 and 32, double
@@ -199,6 +202,10 @@ BatchEntry entry_of(const tsenor_problem& p, char* ws) {
   dp.transpose = (p.flags & TSENOR_FLAG_COLS_FIRST) ? 1 : 0;
   dp.L = p.local_search_steps;
   dp.strict = (p.flags & TSENOR_FLAG_STRICT_PAPER) ? 1 : 0;
+  if (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) {
+    dp.L = 0;  // the simple arm has no local search: the last kernel only writes the mask
+    dp.strict = 1;
+  }
   dp.tau = p.tau;
   dp.tau_mode = p.tau_mode;
   e.rows = p.rows;
@@ -294,7 +301,10 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   }
   mark(2);
   const bool wide = v.greedy ? v.greedy == TSENOR_FLAG_GREEDY_M_LANES : total_blocks < greedy_wide_below_blocks(M);
-  if (wide) {
+  if (v.simple) {
+    if (!assign_groups(b, blocks, kWave)) return TSENOR_ERR_SHAPE;
+    simple_round_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
+  } else if (wide) {
     if (!assign_groups(b, blocks, kWave / M)) return TSENOR_ERR_SHAPE;
     greedy_wide_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
   } else {

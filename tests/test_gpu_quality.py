@@ -1,7 +1,8 @@
 """Solution quality of the HIP path against the exact optimum, and the ablation arms of App. B.2.1.
 
 The arms are reached through the library's own parameters: rounding the entropy solution (T > 0) or the
-importance itself (T = 0), with the full Algorithm 2 or with greedy selection only (strict mode, L = 0).
+importance itself (T = 0), with the full Algorithm 2, with greedy selection only (strict mode, L = 0) or with
+the simple row-then-column rounding (TSENOR_FLAG_SIMPLE_ROUNDING).
 The exact optimum of every block comes from the LP relaxation of Eq. (3) (integral: a capacitated bipartite
 b-matching), solved on the CPU.  Relative error = (f(S*) - f(S)) / f(S*) as in Fig. 3 / Fig. 5.
 
@@ -51,22 +52,39 @@ def test_ablation_arms_against_the_exact_optimum(dev, N, M, block_rows, block_co
     imp = oracle.importance(g["W_f32"], g["col_scale"]).astype(np.float64)
     opt = np.array([exact.lp_optimum(b, N)[0] for b in exact.blocks(imp, M)])
 
-    def arm(iters, greedy_only):
+    def arm(iters, greedy_only, simple=False):
         kw = dict(local_search_steps=0, flags=binding.TSENOR_FLAG_STRICT_PAPER) if greedy_only else {}
-        res = binding.solve(W, N, M, w.tau, iters, col_scale=cs, tau_mode=w.tau_mode, **kw)
+        if simple:
+            kw = dict(flags=binding.TSENOR_FLAG_SIMPLE_ROUNDING)
+        res = binding.solve(W, N, M, w.tau, iters, col_scale=cs, tau_mode=w.tau_mode, want_stats=simple, **kw)
         torch.cuda.synchronize()
         mask = res["mask"].cpu().numpy()
-        if not greedy_only:
+        if simple:
+            # the arm itself against its definition: row-wise then column-wise top-N of the oracle's plan
+            te = oracle.tau_eff(imp.astype(np.float32), w.tau, w.tau_mode)
+            key = oracle.dykstra(imp.astype(np.float32), N, M, te, iters) if iters else imp
+            want = oracle.simple_round(key, N, M)
+            assert np.array_equal(mask, want)
+            missing = N * mask.shape[0] * mask.shape[1] // M - int(mask.sum())
+            assert res["stats"].cpu().numpy().tolist() == [missing, 0, 0, missing]
+        elif not greedy_only:
             assert exact.is_transposable_nm(mask, N, M)
-        return _relative_errors(mask, imp, opt, M, feasible=not greedy_only).mean()
+        return _relative_errors(mask, imp, opt, M, feasible=not (greedy_only or simple)).mean()
 
     print(f"[case] ablation arms {N}:{M}, {len(opt)} blocks", flush=True)
     entropy_optround = arm(300, False)      # the method
     entropy_greedy = arm(300, True)         # "Entropy + Greedy"
     direct_optround = arm(0, False)         # Algorithm 2 on the importance itself
     direct_greedy = arm(0, True)            # greedy selection on the importance itself
+    entropy_simple = arm(300, False, simple=True)   # "Entropy" of Fig. 3 / "Entropy + Simple" of Fig. 5
+    direct_simple = arm(0, False, simple=True)
     print(f"  mean relative error: entropy+optround {entropy_optround:.5f}, entropy+greedy {entropy_greedy:.5f}, "
-          f"optround {direct_optround:.5f}, greedy {direct_greedy:.5f}", flush=True)
+          f"entropy+simple {entropy_simple:.5f}, optround {direct_optround:.5f}, greedy {direct_greedy:.5f}, "
+          f"simple {direct_simple:.5f}", flush=True)
+    # the rounding of Algorithm 2 beats simple rounding by a wide margin on either key (Sec. 5.1, App. B.2.1)
+    assert entropy_optround < 0.5 * entropy_simple
+    assert direct_optround < 0.5 * direct_simple
+    assert entropy_greedy < entropy_simple and direct_greedy < direct_simple
     # local search improves on greedy selection, with and without the entropy solution (App. B.2.1)
     assert entropy_optround < entropy_greedy
     assert direct_optround < direct_greedy

@@ -454,3 +454,30 @@ def test_objective_packing_and_safeguard():
     if r2["objective_prev"] > r2["objective_new"]:
         assert r2["used_prev"] and np.array_equal(r2["mask"], best) and r2["objective"] == r2["objective_prev"]
         assert np.array_equal(r2["pruned"], W * best)
+
+
+def test_simple_rounding_arm():
+    # App. B.2.1 "Simple": row-wise then column-wise N:M rounding.  Pins: a hand-worked 4x4 case, the bounds
+    # every result obeys, and agreement with the full method where the answer is forced.
+    key = np.array([[9, 8, 1, 0], [7, 6, 5, 0], [4, 3, 2, 1], [9, 9, 9, 9]], dtype=np.float64)
+    # rows keep {0,1}, {0,1}, {0,1}, {0,1} (the tie in the last row goes to the lower columns); column 0 then
+    # keeps its two largest of 9, 7, 4, 9 -> rows 0 and 3 (the tie 9 = 9 is no issue: both are kept), column 1
+    # of 8, 6, 3, 9 -> rows 3 and 0
+    want = np.array([[1, 1, 0, 0], [0, 0, 0, 0], [0, 0, 0, 0], [1, 1, 0, 0]], dtype=np.uint8)
+    assert np.array_equal(oracle.simple_round(key, 2, 4), want)
+    rng = np.random.Generator(np.random.Philox(4321))
+    key = rng.standard_normal((16, 24))
+    got = oracle.simple_round(key, 3, 8)
+    b = exact.blocks(got, 8)
+    assert b.sum(axis=2).max() <= 3 and b.sum(axis=1).max() <= 3
+    # every column that was offered at least N row-survivors is full
+    kb = exact.blocks(key, 8)
+    for blk, m in zip(kb, b):
+        survivors = np.zeros_like(m)
+        for i in range(8):
+            survivors[i, np.argsort(-blk[i], kind="stable")[:3]] = 1
+        assert np.array_equal(m.sum(axis=0), np.minimum(survivors.sum(axis=0), 3))
+        assert np.all(m <= survivors)
+    # a key whose N largest entries per row already form a transposable pattern is returned as that pattern
+    perm = np.kron(np.eye(2), np.ones((2, 2)))
+    assert np.array_equal(oracle.simple_round(perm + 0.01 * rng.random((4, 4)), 2, 4), perm.astype(np.uint8))
