@@ -1,12 +1,18 @@
 // Transposable N:M mask finder for MI355X (gfx950): C ABI, host-side launch logic and the small kernels.
 //
-// One call enqueues, on the caller's stream:
-//   1. init_kernel / absmax_kernel      workspace reset; importance maximum of the matrix (relative tau only)
+// One call enqueues, on the caller's stream, for every group of matrices that share a block size and a
+// kernel variant (a single matrix is a group of one):
+//   1. init_kernel / absmax_kernel      workspace reset; importance maximum of every matrix (relative tau only)
 //   2. dykstra_sort_kernel              tile load, all T Dykstra iterations of Algorithm 1 on chip, sort of
 //                                       the M*M plan entries of every block; writes the greedy scan order
 //                                       (and the plan if asked for)                       [dykstra_sort.hpp]
-//   3. greedy_kernel                    Algorithm 2 lines 1-6, one lane per block         [rounding.hpp]
+//   3. greedy_kernel                    Algorithm 2 lines 1-6, one lane per block (greedy_wide_kernel: M lanes
+//                                       per block, for small launches; simple_round_kernel: the ablation arm)
+//                                                                                         [rounding.hpp]
 //   4. finalize_kernel                  Algorithm 2 lines 7-13 (local search), mask write [rounding.hpp]
+//   5. objective_kernel, emit_kernel, stats_kernel   optional outputs
+// Every kernel takes the table of the group by value and finds the matrix of a workgroup from a prefix of
+// workgroup counts.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
