@@ -51,31 +51,46 @@ __global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
   float m = 0.0f;
   if (e.absmax_vec) {
     const int64_t vpr = p.cols / 8;  // 8-weight vectors per row
-    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
-      for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < vpr; v += (int64_t)gridDim.x * blockDim.x) {
-        float w[8];
+    constexpr int kInFlight = 4;     // rows read per thread before any is used
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < vpr; v += (int64_t)gridDim.x * blockDim.x) {
+      float c[8] = {1.0f, 1.0f, 1.0f, 1.0f, 1.0f, 1.0f, 1.0f, 1.0f};  // times exactly 1 where there is no scale
+      if (p.col_scale) {
+        const float4* cs = reinterpret_cast<const float4*>(p.col_scale + v * 8);
+        const float4 a = cs[0], b = cs[1];
+        c[0] = a.x, c[1] = a.y, c[2] = a.z, c[3] = a.w, c[4] = b.x, c[5] = b.y, c[6] = b.z, c[7] = b.w;
+      }
+      for (int64_t r = blockIdx.y; r < rows; r += (int64_t)kInFlight * gridDim.y) {
         if (p.dtype == TSENOR_BF16) {
-          const uint4 raw = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned short*>(p.W) + r * p.ld + v * 8);
-          const unsigned int u[4] = {raw.x, raw.y, raw.z, raw.w};
+          uint4 raw[kInFlight];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            w[2 * k] = __uint_as_float(u[k] << 16);
-            w[2 * k + 1] = __uint_as_float(u[k] & 0xFFFF0000u);
+          for (int u = 0; u < kInFlight; ++u) {
+            const int64_t ru = r + (int64_t)u * gridDim.y < rows ? r + (int64_t)u * gridDim.y : r;
+            raw[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned short*>(p.W) + ru * p.ld + v * 8);
+          }
+#pragma unroll
+          for (int u = 0; u < kInFlight; ++u) {
+            const unsigned int w[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              m = fmaxf(m, fabsf(__uint_as_float(w[k] << 16)) * c[2 * k]);
+              m = fmaxf(m, fabsf(__uint_as_float(w[k] & 0xFFFF0000u)) * c[2 * k + 1]);
+            }
           }
         } else {
-          const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.W) + r * p.ld + v * 8);
-          const float4 a = src[0], b = src[1];
-          w[0] = a.x, w[1] = a.y, w[2] = a.z, w[3] = a.w, w[4] = b.x, w[5] = b.y, w[6] = b.z, w[7] = b.w;
-        }
-        if (p.col_scale) {
-          const float4* cs = reinterpret_cast<const float4*>(p.col_scale + v * 8);
-          const float4 a = cs[0], b = cs[1];
-          const float c[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+          float4 lo[kInFlight], hi[kInFlight];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(w[k]) * c[k]);
-        } else {
+          for (int u = 0; u < kInFlight; ++u) {
+            const int64_t ru = r + (int64_t)u * gridDim.y < rows ? r + (int64_t)u * gridDim.y : r;
+            const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.W) + ru * p.ld + v * 8);
+            lo[u] = src[0];
+            hi[u] = src[1];
+          }
 #pragma unroll
-          for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(w[k]));
+          for (int u = 0; u < kInFlight; ++u) {
+            const float w[8] = {lo[u].x, lo[u].y, lo[u].z, lo[u].w, hi[u].x, hi[u].y, hi[u].z, hi[u].w};
+#pragma unroll
+            for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(w[k]) * c[k]);
+          }
         }
       }
     }
@@ -277,7 +292,7 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   }
   mark(0);
   init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
-  if (any_rel) absmax_kernel<<<strided_grid(b, false, 1024), 256, 0, stream>>>(b);
+  if (any_rel) absmax_kernel<<<strided_grid(b, false, 2048), 256, 0, stream>>>(b);
   mark(1);
   constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
   const auto blocks = [](const BatchEntry& e) { return e.p.nblocks; };
