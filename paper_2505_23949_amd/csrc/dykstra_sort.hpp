@@ -3,7 +3,8 @@
 // How Algorithm 1 is evaluated.  With A = log S + log Q, the cap step (lines 5-6) gives
 // log S = min(A, 0) and log Q = max(A, 0) after every iteration, and one iteration adds a row term
 // and a column term to A.  So A = K + f_i + g_j with K = tau_eff * importance: the whole Dykstra
-// state of a block is K plus 2M potentials.  The kernel keeps kappa = exp(K - max K) and the scalings
+// state of a block is K plus 2M potentials.  The kernel keeps kappa_ij = exp(K_ij - max_j K_ij) (the
+// first row scaling makes a per-row factor of the start irrelevant) and the scalings
 // U_i = exp(f_i), V_j = exp(g_j) and iterates
 //     e_ij = min(kappa_ij V_j U_i, 1);   R_i = N / sum_j e_ij;   C_j = N / sum_i e_ij R_i;
 //     U_i *= R_i;   V_j *= C_j
@@ -18,7 +19,7 @@
 // instead of two) on kappa32 = fl32(kappa U V) with fp32 scalings relative to the double ones, which are
 // kept as logarithms.  fp32 has 8 exponent bits, so every kChunk iterations the relative scalings are
 // checked and, when one has drifted past 2^+-kDriftBits, their logarithms are added to the double ones and
-// kappa32 is rebuilt as fl32(exp(K - max K + log U + log V)) from a fresh read of the importance (kappa
+// kappa32 is rebuilt as fl32(exp(K - row max + log U + log V)) from a fresh read of the importance (kappa
 // itself is not kept: the kernel is budgeted 168 registers).  Rebuilt entries are clamped to about
 // [2^-120, 2^80]; within the drift bound (2^+-80 for a product of a row and a column scaling) a clamped
 // entry is still >= 1 (capped) or <= 2^-40 (nothing).
@@ -154,6 +155,22 @@ __device__ __forceinline__ void all_gather_x(real (&v)[TH]) {
     all_gather_x<T, real, TH, S - 1>(v);
   }
 }
+// Maximum over the lanes of a lane-row of a value per tile row (all TH registers, butterfly): afterwards
+// every lane holds the maximum of each of its tile rows.
+template <class T, int TH, int S = 0>
+__device__ __forceinline__ void all_reduce_max_x(float (&v)[TH]) {
+  if constexpr (S < T::NX) {
+    constexpr int SH = ilog2(TH) - T::NX;
+    constexpr int am = shift_lane(T::XM[S], SH) & (TH - 1);
+    float o[TH];
+#pragma unroll
+    for (int a = 0; a < TH; ++a) o[a] = lane_xor<T::XM[S]>(v[a ^ am]);
+#pragma unroll
+    for (int a = 0; a < TH; ++a) v[a] = fmaxf(v[a], o[a]);
+    all_reduce_max_x<T, TH, S + 1>(v);
+  }
+}
+
 // The same over the lanes of a lane-column; step s pairs lanes that differ in lane bit YM[s].
 template <class T, class real, int TW, int S = 0>
 __device__ __forceinline__ void reduce_scatter_y(real (&v)[TW]) {
@@ -410,7 +427,12 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
   constexpr int NA = (FAST && TH >= 8) ? TH / 2 : TH;
 
   double kap[TH][TW];
-  double mx = 0.0;
+  // Normaliser of every in-kernel row: kappa = exp(K - mrow) <= ~1.  Any per-row constant gives the same
+  // iterates, because the first step of Algorithm 1 rescales every row (with TSENOR_FLAG_COLS_FIRST: every
+  // column, which is the in-kernel row); a single precision value a little above the row's largest K is
+  // enough.  Per row rather than per block, so that one huge entry does not push the other rows of its
+  // block below the range of a double.
+  float mrow[TH];
   {
     const auto addr = addr_of(fresh(rx), fresh(ry));
     auto rows = [&](auto first) {
@@ -422,13 +444,14 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
 #pragma unroll
         for (int b = 0; b < TW; ++b) {
           kap[A0 + a][b] = tau_eff * (double)imp[a][b];  // K of Algorithm 1 line 1
-          mx = fmax(mx, kap[A0 + a][b]);
+          const float up = __double2float_ru(kap[A0 + a][b]);
+          mrow[A0 + a] = b == 0 ? up : fmaxf(mrow[A0 + a], up);
         }
     };
     rows(std::integral_constant<int, 0>{});
     if constexpr (NA < TH) rows(std::integral_constant<int, NA>{});
   }
-  mx = group_max<LPB>(mx);
+  all_reduce_max_x<T, TH>(mrow);
 
   double c[E];  // sort keys
   if constexpr (ZERO_T) {
@@ -451,7 +474,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
     for (int a = 0; a < TH; ++a)
 #pragma unroll
       for (int b = 0; b < TW; ++b) {
-        kap[a][b] = exp(fmax(kap[a][b] - mx, kMinLogKernel));
+        kap[a][b] = exp(fmax(kap[a][b] - (double)mrow[a], kMinLogKernel));
         __builtin_amdgcn_sched_barrier(0);  // one exp at a time: interleaving them only costs registers
       }
 
@@ -511,7 +534,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
 #pragma unroll
               for (int b = 0; b < TW; ++b) {
                 const double K = tau_eff * (double)imp[a][b];
-                const double full = fmax(K - mx, kMinLogKernel) + (lu[A0 + a] + lv[b]);
+                const double full = fmax(K - (double)mrow[A0 + a], kMinLogKernel) + (lu[A0 + a] + lv[b]);
                 kap32[A0 + a][b] = (float)exp(fmin(fmax(full, kLogFloor32), kLogCeil32));
                 __builtin_amdgcn_sched_barrier(0);
               }
@@ -574,7 +597,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
           const int ri = gy * TH + ((A0 + a) ^ rx2), cj = gx * TW + (b ^ ry2);
           const double K = tau_eff * (double)imp[a][b];
           // log S^(T) = min(K + f_i + g_j, 0)
-          const double key = fmin(fmax(K - mx, kMinLogKernel) + (lu[A0 + a] + lv[b]), 0.0);
+          const double key = fmin(fmax(K - (double)mrow[A0 + a], kMinLogKernel) + (lu[A0 + a] + lv[b]), 0.0);
           if (plan_out && active) plan_out[(r0 + mat_row(ri, cj)) * p.cols + c0 + mat_col(ri, cj)] = exp(key);
           const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
           const unsigned long long bits = (unsigned long long)__double_as_longlong(fabs(key));

@@ -55,15 +55,4 @@ __device__ __forceinline__ float lane_xor(float v) {
   return __int_as_float(lane_xor_i32<MASK>(__float_as_int(v)));
 }
 
-// max over the lanes of a group of LPB consecutive lanes (LPB a power of two)
-template <int LPB, int STEP = 1>
-__device__ __forceinline__ double group_max(double v) {
-  if constexpr (STEP < LPB) {
-    v = fmax(v, lane_xor<STEP>(v));
-    return group_max<LPB, STEP * 2>(v);
-  } else {
-    return v;
-  }
-}
-
 }  // namespace tsenor_dev

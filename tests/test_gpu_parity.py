@@ -254,6 +254,46 @@ def test_both_tilings_of_the_dykstra_kernel(dev, M, N, dtype):
             assert np.array_equal(got["mask"], ref["mask"])
 
 
+@pytest.mark.parametrize("M,N", [(8, 4), (16, 8), (32, 16), (64, 32)])
+def test_zero_blocks_outliers_and_zero_scales(dev, M, N):
+    # blocks that are entirely zero (every plan entry ties: index order), outliers 1e4 times the typical weight
+    # (they set the matrix maximum, so ordinary blocks get a nearly flat kernel), and columns whose scale is zero
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    rng = np.random.Generator(np.random.Philox(8800 + M))
+    rows, cols = 4 * M, 5 * M
+    Wf = (0.02 * rng.standard_normal((rows, cols))).astype(np.float32)
+    Wf[M:2 * M, 2 * M:3 * M] = 0.0
+    Wf[3 * M:, :M] = 0.0
+    Wf[0, 0], Wf[2 * M + 1, 4 * M + 3] = 200.0, -150.0
+    cs = rng.lognormal(0.0, 1.0, cols).astype(np.float32)
+    cs[M + 2] = 0.0
+    cs[3 * M:3 * M + 3] = 0.0
+    W, csd = torch.from_numpy(Wf).to(dev), torch.from_numpy(cs).to(dev)
+    for tau, mode, iters in ((0.005, 1, 200), (0.02, 1, 60), (25.0, 0, 100)):
+        for flags in (0, binding.TSENOR_FLAG_COLS_FIRST):
+            print(f"[case] zero blocks / outliers {N}:{M} tau={tau} mode={mode} T={iters} flags={flags}", flush=True)
+            res = binding.solve(W, N, M, tau, iters, col_scale=csd, tau_mode=mode, flags=flags, want_plan=True,
+                                want_stats=True)
+            torch.cuda.synchronize()
+            ref = oracle.mask(Wf, N, M, tau, iters, col_scale=cs, tau_mode=mode, cols_first=bool(flags),
+                              return_plan=True)
+            plan = res["plan"].cpu().numpy()
+            assert np.isfinite(plan).all()
+            assert np.abs(plan - np.exp(ref["log_S"])).max() <= PLAN_ATOL
+            mask = res["mask"].cpu().numpy()
+            assert exact.is_transposable_nm(mask, N, M)
+            same = (exact.blocks(mask, M) == exact.blocks(ref["mask"], M)).all(axis=(1, 2))
+            # blocks with zero columns hold mathematically tied entries after the iterations; the all-zero blocks
+            # and the ordinary ones must agree exactly
+            tied = np.zeros(same.shape, dtype=bool).reshape(rows // M, cols // M)
+            tied[:, 1] = tied[:, 3] = True
+            assert same[~tied.reshape(-1)].all(), np.flatnonzero(~same)
+            assert res["tau_eff"].cpu().numpy()[0] == ref["tau_eff"]
+
+
 def test_zero_iterations_rounds_the_importance(dev):
     from dataclasses import replace
 
