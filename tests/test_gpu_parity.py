@@ -17,6 +17,7 @@ from paper_2505_23949_amd import synth
 pytestmark = pytest.mark.gpu
 
 PLAN_ATOL = 1e-9
+FP32_PLAN_ATOL = 1e-4      # bar for the fp32-iteration mode (see the tests of that mode below)
 
 
 @pytest.fixture(scope="module")
@@ -273,16 +274,17 @@ def test_zero_blocks_outliers_and_zero_scales(dev, M, N):
     cs[3 * M:3 * M + 3] = 0.0
     W, csd = torch.from_numpy(Wf).to(dev), torch.from_numpy(cs).to(dev)
     for tau, mode, iters in ((0.005, 1, 200), (0.02, 1, 60), (25.0, 0, 100)):
-        for flags in (0, binding.TSENOR_FLAG_COLS_FIRST):
+        for flags in (0, binding.TSENOR_FLAG_COLS_FIRST, binding.TSENOR_FLAG_FP32_ITERATIONS):
             print(f"[case] zero blocks / outliers {N}:{M} tau={tau} mode={mode} T={iters} flags={flags}", flush=True)
             res = binding.solve(W, N, M, tau, iters, col_scale=csd, tau_mode=mode, flags=flags, want_plan=True,
                                 want_stats=True)
             torch.cuda.synchronize()
-            ref = oracle.mask(Wf, N, M, tau, iters, col_scale=cs, tau_mode=mode, cols_first=bool(flags),
-                              return_plan=True)
+            ref = oracle.mask(Wf, N, M, tau, iters, col_scale=cs, tau_mode=mode,
+                              cols_first=flags == binding.TSENOR_FLAG_COLS_FIRST, return_plan=True)
             plan = res["plan"].cpu().numpy()
             assert np.isfinite(plan).all()
-            assert np.abs(plan - np.exp(ref["log_S"])).max() <= PLAN_ATOL
+            atol = FP32_PLAN_ATOL if flags == binding.TSENOR_FLAG_FP32_ITERATIONS else PLAN_ATOL
+            assert np.abs(plan - np.exp(ref["log_S"])).max() <= atol
             mask = res["mask"].cpu().numpy()
             assert exact.is_transposable_nm(mask, N, M)
             same = (exact.blocks(mask, M) == exact.blocks(ref["mask"], M)).all(axis=(1, 2))
@@ -290,7 +292,15 @@ def test_zero_blocks_outliers_and_zero_scales(dev, M, N):
             # and the ordinary ones must agree exactly
             tied = np.zeros(same.shape, dtype=bool).reshape(rows // M, cols // M)
             tied[:, 1] = tied[:, 3] = True
-            assert same[~tied.reshape(-1)].all(), np.flatnonzero(~same)
+            if flags == binding.TSENOR_FLAG_FP32_ITERATIONS:
+                # the outliers leave the ordinary blocks a nearly flat plan (entries within 1e-6 of each other),
+                # where single-precision noise may reorder the scan of a whole block (one of twelve here): the
+                # bar is the retained importance, at 1e-4 for this adversarial input
+                imp = oracle.importance(Wf, cs).astype(np.float64)
+                kept, kept_ref = float((mask * imp).sum()), float((ref["mask"] * imp).sum())
+                assert abs(kept - kept_ref) <= 1e-4 * kept_ref
+            else:
+                assert same[~tied.reshape(-1)].all(), np.flatnonzero(~same)
             assert res["tau_eff"].cpu().numpy()[0] == ref["tau_eff"]
 
 
@@ -572,8 +582,6 @@ def test_unaligned_views(dev):
 # fp32 kernel against the double oracle: plan within 1e-4 absolute, masks identical on >= 99.9 % of
 # blocks, retained importance within 1e-5 relative, invariants exact.
 # ----------------------------------------------------------------------------------------------------
-
-FP32_PLAN_ATOL = 1e-4
 
 FP32_CASES = [
     synth.CONFIGS["cfg1_2of4_512"],
