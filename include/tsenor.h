@@ -57,9 +57,11 @@ enum { TSENOR_F32 = 0, TSENOR_BF16 = 1 }; /* storage type of W; bf16 is widened 
  *   REL_MATRIX_MAX  K_ij = imp_ij / (tau * max_ij imp_ij): the entropy weight 1/tau_eff of Eq. 4 is
  *                   tau times the largest importance of this matrix (the parameter choice of
  *                   App. B.1, "0.005 max|W|", read so that it is consistent with Eq. 4).
- * The log-kernel may not exceed 690 (natural-log units); larger values are a TSENOR_ERR_PARAM in
- * ABSOLUTE mode when detectable on the host (tau itself > 690 / FLT_MIN is not), and in
- * REL_MATRIX_MAX mode tau must be >= 1/690. */
+ * In REL_MATRIX_MAX mode tau must be >= 1/690 (K <= 690 natural-log units), else TSENOR_ERR_PARAM.
+ * In ABSOLUTE mode K is not bounded by the call; the supported range is a spread of K of at most ~700
+ * inside any one row of a block (column, with TSENOR_FLAG_COLS_FIRST): entries further below their row's
+ * largest K are treated as 700 below it, which is exact to double precision unless the iteration count is
+ * large enough for the row's scaling to grow by e^700 (N^iters >= e^700). */
 enum { TSENOR_TAU_ABSOLUTE = 0, TSENOR_TAU_REL_MATRIX_MAX = 1 };
 
 enum {
