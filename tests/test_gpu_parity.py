@@ -98,6 +98,8 @@ CASES = [
     synth.Workload("m16_5of16_t", 64, 64, 5, 16, 0.004, 80, "f32", "student_t", 79),
     synth.Workload("m32_1of32", 64, 96, 1, 32, 0.01, 60, "f32", "normal", 80),
     synth.Workload("m32_31of32", 64, 96, 31, 32, 0.01, 60, "f32", "normal", 81),
+    synth.Workload("m32_long_run", 64, 96, 16, 32, 0.005, 2000, "f32", "student_t", 85),  # far past convergence
+    synth.Workload("m64_long_run", 64, 128, 32, 64, 0.002, 1500, "bf16", "wanda", 86),
 ]
 
 
@@ -593,6 +595,7 @@ FP32_CASES = [
     synth.Workload("m32_few_iters", 64, 96, 16, 32, 0.005, 5, "f32", "normal", 82),      # T below the warm-up
     synth.Workload("m32_nine_iters", 64, 96, 16, 32, 0.005, 9, "f32", "normal", 83),     # one fp32 iteration
     synth.Workload("m16_hard", 128, 128, 8, 16, 0.0015, 300, "f32", "student_t", 84),    # logits up to 667
+    synth.Workload("m32_long_run", 64, 96, 16, 32, 0.005, 2000, "f32", "student_t", 85),
 ]
 
 
