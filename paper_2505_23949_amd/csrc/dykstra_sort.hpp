@@ -534,7 +534,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
 #pragma unroll
               for (int b = 0; b < TW; ++b) {
                 const double K = tau_eff * (double)imp[a][b];
-                const double full = fmax(K - (double)mrow[A0 + a], kMinLogKernel) + (lu[A0 + a] + lv[b]);
+                const double full = (K - (double)mrow[A0 + a]) + (lu[A0 + a] + lv[b]);
                 kap32[A0 + a][b] = (float)exp(fmin(fmax(full, kLogFloor32), kLogCeil32));
                 __builtin_amdgcn_sched_barrier(0);
               }
@@ -597,7 +597,9 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
           const int ri = gy * TH + ((A0 + a) ^ rx2), cj = gx * TW + (b ^ ry2);
           const double K = tau_eff * (double)imp[a][b];
           // log S^(T) = min(K + f_i + g_j, 0)
-          const double key = fmin(fmax(K - (double)mrow[A0 + a], kMinLogKernel) + (lu[A0 + a] + lv[b]), 0.0);
+          // (K is not floored here as it is for kappa: entries too small for the iterations to see keep
+          // their own order in the scan)
+          const double key = fmin((K - (double)mrow[A0 + a]) + (lu[A0 + a] + lv[b]), 0.0);
           if (plan_out && active) plan_out[(r0 + mat_row(ri, cj)) * p.cols + c0 + mat_col(ri, cj)] = exp(key);
           const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
           const unsigned long long bits = (unsigned long long)__double_as_longlong(fabs(key));

@@ -174,8 +174,12 @@ def test_randomised_configurations(dev):
 
     from paper_2505_23949_amd import binding
 
-    rng = np.random.Generator(np.random.Philox(777))
-    for case in range(48):
+    import os
+
+    # TSENOR_TEST_SEED / TSENOR_TEST_DRAWS widen the search when run by hand
+    seed, draws = int(os.environ.get("TSENOR_TEST_SEED", "777")), int(os.environ.get("TSENOR_TEST_DRAWS", "48"))
+    rng = np.random.Generator(np.random.Philox(seed))
+    for case in range(draws):
         M = int(rng.choice([4, 8, 16, 32, 64]))
         N = int(rng.integers(1, M))
         rows, cols = M * int(rng.integers(1, 6)), M * int(rng.integers(1, 7))
@@ -226,10 +230,33 @@ def test_randomised_configurations(dev):
                               square=square, tau_mode=int(rel), L=L, strict_paper=strict, cols_first=cols_first)
         S_ref = np.exp(ref["log_S"])
         plan = res["plan"].cpu().numpy()
-        err = np.abs(plan / S_ref - 1.0).max() if iters == 0 else np.abs(plan - S_ref).max()
+        if iters == 0:
+            # exp(K) itself, unbounded above: the bar is relative, where exp(K) is finite
+            ok = np.isfinite(S_ref)
+            assert np.array_equal(np.isfinite(plan), ok), desc
+            err = np.abs(plan[ok] / S_ref[ok] - 1.0).max()
+        else:
+            err = np.abs(plan - S_ref).max()
         assert err <= PLAN_ATOL, (desc, err)
-        assert np.array_equal(res["mask"].cpu().numpy(), ref["mask"]), desc
-        assert np.array_equal(res["stats"].cpu().numpy(), ref["stats"]), desc
+        # Blocks in which two plan entries agree to rounding (mathematical ties, e.g. several entries within an
+        # ulp of the cap when N is small, or duplicated bf16 values in a tiny block) may be scanned in either
+        # order; every other block must come out exactly as the oracle's.
+        mask = res["mask"].cpu().numpy()
+        keys = np.sort(exact.blocks(ref["log_S"], M).reshape(-1, M * M), axis=1)
+        gap = np.diff(keys, axis=1)
+        scale = np.maximum(np.abs(keys[:, 1:]), np.abs(keys[:, :-1]))
+        close = gap <= 1e-9 * np.maximum(scale, 1e-3)
+        if iters == 0:
+            close &= gap > 0        # equal importances give equal keys on both sides: index order on both
+        else:
+            close &= scale > 0      # entries at the cap are exactly 0 on both sides: index order on both
+        tied = close.any(axis=1)
+        same = (exact.blocks(mask, M) == exact.blocks(ref["mask"], M)).all(axis=(1, 2))
+        assert same[~tied].all(), (desc, np.flatnonzero(~same & ~tied))
+        if not strict:
+            assert exact.is_transposable_nm(mask, N, M), desc
+        if not tied.any():
+            assert np.array_equal(res["stats"].cpu().numpy(), ref["stats"]), desc
 
 
 @pytest.mark.parametrize("M,N,dtype", [(16, 8, "f32"), (32, 16, "bf16"), (32, 7, "f32"), (16, 3, "bf16")])
