@@ -192,6 +192,7 @@ def test_randomised_configurations(dev):
         L = int(rng.choice([0, 1, 10]))
         greedy = int(rng.choice([0, binding.TSENOR_FLAG_GREEDY_ONE_LANE, binding.TSENOR_FLAG_GREEDY_M_LANES]))
         greedy |= int(rng.choice([0, binding.TSENOR_FLAG_TILES_LARGE, binding.TSENOR_FLAG_TILES_SMALL]))
+        fp32 = bool(rng.integers(0, 4) == 0)
         dist = rng.choice(["normal", "student_t", "few_levels"])
         if dist == "normal":
             Wf = (0.02 * rng.standard_normal((rows, cols))).astype(np.float32)
@@ -218,9 +219,10 @@ def test_randomised_configurations(dev):
         csd = None if cs is None else torch.from_numpy(cs).to(dev)
         tau = 0.01 if rel else 30.0
         flags = (binding.TSENOR_FLAG_STRICT_PAPER if strict else 0) | \
-                (binding.TSENOR_FLAG_COLS_FIRST if cols_first else 0) | greedy
+                (binding.TSENOR_FLAG_COLS_FIRST if cols_first else 0) | greedy | \
+                (binding.TSENOR_FLAG_FP32_ITERATIONS if fp32 else 0)
         desc = (f"case {case}: {N}:{M} {rows}x{cols}+{pad} bf16={bf16} cs={use_cs} add={use_add} sq={square} rel={rel} "
-                f"T={iters} strict={strict} L={L} cols_first={cols_first} greedy={greedy} {dist}")
+                f"T={iters} strict={strict} L={L} cols_first={cols_first} greedy={greedy} fp32={fp32} {dist}")
         print(f"[case] {desc}", flush=True)
         res = binding.solve(W, N, M, tau, iters, col_scale=csd, tau_mode=int(rel), local_search_steps=L, flags=flags,
                             add=add, add_scale=0.5, want_plan=True, want_stats=True,
@@ -237,6 +239,16 @@ def test_randomised_configurations(dev):
             err = np.abs(plan[ok] / S_ref[ok] - 1.0).max()
         else:
             err = np.abs(plan - S_ref).max()
+        if fp32 and iters > 0:
+            # the fp32-iteration mode: the plan to its own bar and feasibility; which block gets which mask may
+            # differ where plan entries are closer than single-precision noise (the statistical bars of that mode
+            # are checked on the paper-shaped workloads further down)
+            assert err <= FP32_PLAN_ATOL, (desc, err)
+            mask = res["mask"].cpu().numpy()
+            assert set(np.unique(mask)) <= {0, 1}, desc
+            if not strict:
+                assert exact.is_transposable_nm(mask, N, M), desc
+            continue
         assert err <= PLAN_ATOL, (desc, err)
         # Blocks in which two plan entries agree to rounding (mathematical ties, e.g. several entries within an
         # ulp of the cap when N is small, or duplicated bf16 values in a tiny block) may be scanned in either
