@@ -341,7 +341,10 @@ __global__ __launch_bounds__(256) void emit_kernel(Batch batch) {
   uint8_t* mask = e.mask;
   const bool use_prev = prev_mask && e.hdr->use_prev;
   const int64_t per_row = p.cols / 8;
-  for (int64_t r = blockIdx.y; r < rows; r += gridDim.y)
+  // a workgroup handles a contiguous band of rows
+  const int64_t band = (rows + gridDim.y - 1) / gridDim.y;
+  const int64_t r_end = (blockIdx.y + 1) * band < rows ? (blockIdx.y + 1) * band : rows;
+  for (int64_t r = blockIdx.y * band; r < r_end; ++r)
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < per_row; v += (int64_t)gridDim.x * blockDim.x) {
       const int64_t c = v * 8;
       unsigned int bits = 0;

@@ -59,12 +59,15 @@ __global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
         const float4 a = cs[0], b = cs[1];
         c[0] = a.x, c[1] = a.y, c[2] = a.z, c[3] = a.w, c[4] = b.x, c[5] = b.y, c[6] = b.z, c[7] = b.w;
       }
-      for (int64_t r = blockIdx.y; r < rows; r += (int64_t)kInFlight * gridDim.y) {
+      // a workgroup streams a contiguous band of rows (rows far apart cost a page-table walk per load)
+      const int64_t band = (rows + gridDim.y - 1) / gridDim.y;
+      const int64_t r_end = (blockIdx.y + 1) * band < rows ? (blockIdx.y + 1) * band : rows;
+      for (int64_t r = blockIdx.y * band; r < r_end; r += kInFlight) {
         if (p.dtype == TSENOR_BF16) {
           uint4 raw[kInFlight];
 #pragma unroll
           for (int u = 0; u < kInFlight; ++u) {
-            const int64_t ru = r + (int64_t)u * gridDim.y < rows ? r + (int64_t)u * gridDim.y : r;
+            const int64_t ru = r + u < r_end ? r + u : r;
             raw[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned short*>(p.W) + ru * p.ld + v * 8);
           }
 #pragma unroll
@@ -80,7 +83,7 @@ __global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
           float4 lo[kInFlight], hi[kInFlight];
 #pragma unroll
           for (int u = 0; u < kInFlight; ++u) {
-            const int64_t ru = r + (int64_t)u * gridDim.y < rows ? r + (int64_t)u * gridDim.y : r;
+            const int64_t ru = r + u < r_end ? r + u : r;
             const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.W) + ru * p.ld + v * 8);
             lo[u] = src[0];
             hi[u] = src[1];
@@ -99,7 +102,8 @@ __global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
       for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < p.cols; c += (int64_t)gridDim.x * blockDim.x)
         m = fmaxf(m, load_importance(p, r, c));
   }
-  // one atomic per workgroup: thousands of atomics on one address would take longer than the reads
+  // one atomic per workgroup, and only ~512 workgroups per matrix: atomics on one address take ~12 ns each,
+  // so thousands of them would take longer than the reads
   __shared__ float wave_max[4];
   for (int s = 1; s < kWave; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, kWave));
   if ((threadIdx.x & (kWave - 1)) == 0) wave_max[threadIdx.x / kWave] = m;
@@ -292,7 +296,7 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   }
   mark(0);
   init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
-  if (any_rel) absmax_kernel<<<strided_grid(b, false, 2048), 256, 0, stream>>>(b);
+  if (any_rel) absmax_kernel<<<strided_grid(b, false, 512), 256, 0, stream>>>(b);
   mark(1);
   constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
   const auto blocks = [](const BatchEntry& e) { return e.p.nblocks; };
