@@ -3,15 +3,16 @@
 // How Algorithm 1 is evaluated.  With A = log S + log Q, the cap step (lines 5-6) gives
 // log S = min(A, 0) and log Q = max(A, 0) after every iteration, and one iteration adds a row term
 // and a column term to A.  So A = K + f_i + g_j with K = tau_eff * importance: the whole Dykstra
-// state of a block is K plus 2M potentials.  The kernel keeps kappa_ij = exp(K_ij - max_j K_ij) (the
-// first row scaling makes a per-row factor of the start irrelevant) and the scalings
-// U_i = exp(f_i), V_j = exp(g_j) and iterates
-//     e_ij = min(kappa_ij V_j U_i, 1);   R_i = N / sum_j e_ij;   C_j = N / sum_i e_ij R_i;
+// state of a block is K plus 2M potentials.  With kappa_ij = exp(K_ij - max_j K_ij) (the first row
+// scaling makes a per-row factor of the start irrelevant) and the scalings U_i = exp(f_i), V_j = exp(g_j)
+// one iteration is
+//     e_ij = min(kappa_ij U_i V_j, 1);   R_i = N / sum_j e_ij;   C_j = N / sum_i e_ij R_i;
 //     U_i *= R_i;   V_j *= C_j
 // which is lines 3-6 of Algorithm 1 in exact arithmetic: the row scaling acts on the plan capped by
 // the previous iteration, the column scaling on the row-scaled plan, and the cap with its dual is the
-// min(., 1) at the top of the next pass (App. A.2 listing, same order of operations).  Four
-// operations per entry and iteration and no transcendental in the loop.
+// min(., 1) at the top of the next pass (App. A.2 listing, same order of operations).  The kernel keeps
+// kappa_ij U_i as one number per entry (updated by R_i every iteration), so an iteration costs four
+// operations per entry - multiply-and-clamp, add, fused multiply-add, multiply - and no transcendental.
 //
 // Precision.  Default: everything in double (MI355X issues fp64 vector operations at 16 lanes/clk/SIMD),
 // which reproduces a double-precision reference to ~1e-13.  FAST: the first kWarmIters iterations in
@@ -205,14 +206,18 @@ __device__ __forceinline__ int reg_xor_y(int q) {
     return 0;
 }
 
-// One iteration of Algorithm 1 (lines 3-6) on the register tile of this lane.  `floor_` bounds the sums
-// from below (keeps the scalings finite on degenerate input).  STORE keeps the capped entries of the row
-// pass for the column pass; otherwise they are recomputed from an opaque copy of V (for tiles too large
-// to hold twice: without the copy the compiler keeps the row pass's values alive and spills them).
-template <class T, bool STORE, class real, int TH, int TW>
-__device__ __forceinline__ void dykstra_iteration(const real (&kap)[TH][TW], real (&U)[TH], real (&V)[TW], real Nd,
+// One iteration of Algorithm 1 (lines 3-6) on the register tile of this lane.  The row scalings are folded
+// into the tile as they are found (kap holds kappa_ij U_i), so an entry costs one multiply with its column
+// scaling, and only the scalings of the rows this lane owns are kept as numbers (Uown, for the potentials at
+// the end).  `floor_` bounds the sums from below (keeps the scalings finite on degenerate input).  STORE
+// keeps the capped entries of the row pass for the column pass; otherwise they are recomputed from an
+// opaque copy of V (for tiles too large to hold twice: without the copy the compiler keeps the row pass's
+// values alive and spills them).
+template <class T, bool STORE, class real, int TH, int TW, int OR>
+__device__ __forceinline__ void dykstra_iteration(real (&kap)[TH][TW], real (&Uown)[OR], real (&V)[TW], real Nd,
                                                   real floor_) {
   constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
+  static_assert(OR == OWN_R, "one scaling per owned row");
   real e[STORE ? TH : 1][STORE ? TW : 1];
   real R[TH], C[TW];
   // projection onto C1 (line 3) of the plan capped by the previous iteration
@@ -221,7 +226,7 @@ __device__ __forceinline__ void dykstra_iteration(const real (&kap)[TH][TW], rea
     real s = 0;
 #pragma unroll
     for (int b = 0; b < TW; ++b) {
-      const real ev = clamp01((kap[a][b] * V[b]) * U[a]);
+      const real ev = clamp01(kap[a][b] * V[b]);
       if constexpr (STORE) e[a][b] = ev;
       s = b == 0 ? ev : s + ev;  // (0 + x is not a no-op for the compiler: it would keep the add)
     }
@@ -229,7 +234,10 @@ __device__ __forceinline__ void dykstra_iteration(const real (&kap)[TH][TW], rea
   }
   reduce_scatter_x<T, real, TH>(R);
 #pragma unroll
-  for (int a = 0; a < OWN_R; ++a) R[a] = Nd * fast_rcp(vmax(R[a], floor_));
+  for (int a = 0; a < OWN_R; ++a) {
+    R[a] = Nd * fast_rcp(vmax(R[a], floor_));
+    Uown[a] *= R[a];
+  }
   all_gather_x<T, real, TH>(R);
   // projection onto C2 (line 4)
   real Vc[TW];
@@ -247,7 +255,7 @@ __device__ __forceinline__ void dykstra_iteration(const real (&kap)[TH][TW], rea
       if constexpr (STORE)
         ev = e[a][b];
       else
-        ev = clamp01((kap[a][b] * Vc[b]) * U[a]);
+        ev = clamp01(kap[a][b] * Vc[b]);
       s = vfma(ev, R[a], s);
     }
     C[b] = s;
@@ -257,7 +265,9 @@ __device__ __forceinline__ void dykstra_iteration(const real (&kap)[TH][TW], rea
   for (int b = 0; b < OWN_C; ++b) C[b] = Nd * fast_rcp(vmax(C[b], floor_));
   all_gather_y<T, real, TW>(C);
 #pragma unroll
-  for (int a = 0; a < TH; ++a) U[a] *= R[a];
+  for (int a = 0; a < TH; ++a)
+#pragma unroll
+    for (int b = 0; b < TW; ++b) kap[a][b] *= R[a];
 #pragma unroll
   for (int b = 0; b < TW; ++b) V[b] *= C[b];
   // lines 5-6 (cap and dual update) are the clamp at the top of the next pass
@@ -484,21 +494,21 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
     constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
     double lu_own[OWN_R], lv_own[OWN_C];
     {
-      double U[TH], V[TW];
+      double Uown[OWN_R], V[TW];
 #pragma unroll
-      for (int a = 0; a < TH; ++a) U[a] = 1.0;
+      for (int a = 0; a < OWN_R; ++a) Uown[a] = 1.0;
 #pragma unroll
       for (int b = 0; b < TW; ++b) V[b] = 1.0;
       if constexpr (FAST) {
         // the entries are recomputed in the column pass: this phase must fit the registers of the fp32 loop
         const int t_double = p.T < kWarmIters ? p.T : kWarmIters;
-        for (int t = 0; t < t_double; ++t) dykstra_iteration<T, false>(kap, U, V, Nd, 1e-300);
+        for (int t = 0; t < t_double; ++t) dykstra_iteration<T, false>(kap, Uown, V, Nd, 1e-300);
       } else {
-        for (int t = 0; t < p.T; ++t) dykstra_iteration<T, T::STORE_E>(kap, U, V, Nd, 1e-300);
+        for (int t = 0; t < p.T; ++t) dykstra_iteration<T, T::STORE_E>(kap, Uown, V, Nd, 1e-300);
       }
 #pragma unroll
       for (int a = 0; a < OWN_R; ++a) {
-        lu_own[a] = log(U[a]);
+        lu_own[a] = log(Uown[a]);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
