@@ -180,10 +180,10 @@ def main() -> int:
         "stage_ms": {n: round(v, 4) for n, v in zip(binding.STAGE_NAMES, stage_ms)},
     }
     if w.M == 32 and not args.fp32_iterations and w.iters > 0:
-        # second view of the same measurement: vector instructions the loop issues (183 per wave of two
+        # second view of the same measurement: vector instructions the loop issues (169 per wave of two
         # blocks and iteration, counted in the compiled kernel) against the issue slots of the chip at its peak
         # clock (1024 SIMDs, one double-precision wave instruction per 4 cycles, 2.4 GHz)
-        issued = 183.0 * (weights / 2048.0) * w.iters
+        issued = 169.0 * (weights / 2048.0) * w.iters
         roofline["loop_issue_frac_of_peak_clock"] = round(issued / (1024 * (dyk_ms * 1e-3) * 2.4e9 / 4.0), 4)
 
     # host copy of the result for the sample check below
