@@ -291,9 +291,9 @@ __device__ __forceinline__ void dykstra_iteration(real (&kap)[TH][TW], real (&Uo
 //     sum_j e'_ij = (sum_j e_ij) / U_i,  so  U_i R_i = N / sum_j e'_ij   and   sum_i e_ij R_i = sum_i e'_ij (U_i R_i).
 // U, Uinv: scaling of every tile row and its reciprocal; V: scaling of every tile column.  A row scaling
 // grows by at most 2^10 per iteration (keeps everything finite on degenerate input).
-template <class T, int TH, int TW>
+template <class T, bool LDS_GATHER = false, int TH, int TW>
 __device__ __forceinline__ void dykstra_iteration_f32(const float (&kap)[TH][TW], float (&U)[TH], float (&Uinv)[TH],
-                                                      float (&V)[TW], float Nf) {
+                                                      float (&V)[TW], float Nf, float2* xr = nullptr, int rx = 0) {
   constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
   float e[TH][TW], S[TH], C[TW];
 #pragma unroll
@@ -311,12 +311,26 @@ __device__ __forceinline__ void dykstra_iteration_f32(const float (&kap)[TH][TW]
     Un[a] = fminf(Nf * fast_rcp(S[a]), U[a] * 1024.0f);  // new scaling of an owned row
     S[a] = fast_rcp(Un[a]);                              // and its reciprocal
   }
-  all_gather_x<T, float, TH>(Un);
-  all_gather_x<T, float, TH>(S);
+  if constexpr (LDS_GATHER) {
+    // scaling and reciprocal of the owned row through LDS as one pair (see dykstra_iteration)
+    static_assert(OWN_R == 1, "one owned row per lane");
+    xr[rx] = make_float2(Un[0], S[0]);
+    asm volatile("" ::: "memory");
 #pragma unroll
-  for (int a = 0; a < TH; ++a) {
-    U[a] = Un[a];
-    Uinv[a] = S[a];
+    for (int a = 0; a < TH; ++a) {
+      const float2 got = xr[a ^ rx];
+      U[a] = got.x;
+      Uinv[a] = got.y;
+    }
+    asm volatile("" ::: "memory");
+  } else {
+    all_gather_x<T, float, TH>(Un);
+    all_gather_x<T, float, TH>(S);
+#pragma unroll
+    for (int a = 0; a < TH; ++a) {
+      U[a] = Un[a];
+      Uinv[a] = S[a];
+    }
   }
 #pragma unroll
   for (int b = 0; b < TW; ++b) {
@@ -592,7 +606,13 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
         rebuild();
         for (int t = kWarmIters; t < p.T;) {
           const int stop = (p.T - t > kChunk) ? t + kChunk : p.T;
-          for (; t < stop; ++t) dykstra_iteration_f32<T>(kap32, U32, Uinv32, V32, Nf);
+          if constexpr (M == 32 || M == 64) {
+            __shared__ float2 xrows32[WPG][kWave / 8][8];
+            float2* xr = &xrows32[wave_in_group][lane / 8][0];
+            for (; t < stop; ++t) dykstra_iteration_f32<T, true>(kap32, U32, Uinv32, V32, Nf, xr, rx);
+          } else {
+            for (; t < stop; ++t) dykstra_iteration_f32<T>(kap32, U32, Uinv32, V32, Nf);
+          }
           float mxs = U32[0], mns = U32[0];
 #pragma unroll
           for (int a = 1; a < TH; ++a) mxs = fmaxf(mxs, U32[a]), mns = fminf(mns, U32[a]);
