@@ -285,6 +285,15 @@ __device__ __forceinline__ void dykstra_iteration(real (&kap)[TH][TW], real (&Uo
   // lines 5-6 (cap and dual update) are the clamp at the top of the next pass
 }
 
+// min of two floats as the bare instruction.  fminf() makes the compiler quiet possible signalling NaNs in
+// operands it has not computed itself (one extra v_max per value read back from LDS); nothing here is a NaN
+// unless the input was, and then any result will do.
+__device__ __forceinline__ float raw_min(float a, float b) {
+  float r;
+  asm("v_min_f32_e32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
 // The same iteration in single precision, arranged so that every per-entry operation is a plain two- or
 // three-operand fp32 instruction (the clamp output modifier needs the long encoding, which issues at half
 // the fp32 rate).  With e'_ij = min(kappa_ij V_j, 1/U_i) = e_ij / U_i:
@@ -300,7 +309,7 @@ __device__ __forceinline__ void dykstra_iteration_f32(const float (&kap)[TH][TW]
   for (int a = 0; a < TH; ++a) {
 #pragma unroll
     for (int b = 0; b < TW; ++b) {
-      e[a][b] = fminf(kap[a][b] * V[b], Uinv[a]);
+      e[a][b] = raw_min(kap[a][b] * V[b], Uinv[a]);
       S[a] = b == 0 ? e[a][b] : S[a] + e[a][b];
     }
   }
