@@ -509,7 +509,9 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
         const int ri = gy * TH + (a ^ rx0), cj = gx * TW + (b ^ ry0);
         const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
         const unsigned long long bits = (unsigned long long)__double_as_longlong(kap[a][b]);
-        const unsigned long long key = (0x40A0000000000000ull - bits) & ~((1ull << kIdxBits) - 1);
+        // bit patterns of non-negative doubles order like the doubles: pattern(2^1023) - pattern(K) reverses
+        // the order for every finite K >= 0 and is again the pattern of a positive double
+        const unsigned long long key = (0x7FE0000000000000ull - bits) & ~((1ull << kIdxBits) - 1);
         c[a * TW + b] = __longlong_as_double((long long)(key | idx));
         if (plan_out && active)
           plan_out[(r0 + mat_row(ri, cj)) * p.cols + c0 + mat_col(ri, cj)] = exp(kap[a][b]);
