@@ -224,10 +224,26 @@ def test_randomised_configurations(dev):
         desc = (f"case {case}: {N}:{M} {rows}x{cols}+{pad} bf16={bf16} cs={use_cs} add={use_add} sq={square} rel={rel} "
                 f"T={iters} strict={strict} L={L} cols_first={cols_first} greedy={greedy} fp32={fp32} {dist}")
         print(f"[case] {desc}", flush=True)
+        extras = cols % 8 == 0 and bool(rng.integers(0, 3) == 0)
         res = binding.solve(W, N, M, tau, iters, col_scale=csd, tau_mode=int(rel), local_search_steps=L, flags=flags,
-                            add=add, add_scale=0.5, want_plan=True, want_stats=True,
+                            add=add, add_scale=0.5, want_plan=True, want_stats=True, want_packed=extras,
+                            want_pruned=extras, want_objective=extras,
                             importance=binding.TSENOR_IMPORTANCE_SQUARE if square else binding.TSENOR_IMPORTANCE_ABS)
         torch.cuda.synchronize()
+        if extras:
+            # the extra outputs must describe the mask the call returned, whatever that mask is
+            got_mask = res["mask"].cpu().numpy()
+            imp_used, x_used = oracle.importance_ex(Wf, add=Vf if use_add else None, add_scale=0.5, col_scale=cs,
+                                                    square=square)
+            assert np.array_equal(res["packed"].cpu().numpy(), oracle.pack_bits(got_mask)), desc
+            pruned = res["pruned"].float().cpu().numpy()
+            want = x_used * got_mask
+            if bf16:
+                want = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(want))
+            assert np.array_equal(pruned, want), desc
+            obj = float(res["objective"].cpu().numpy()[0])
+            obj_ref = oracle.objective(got_mask, imp_used, M)
+            assert abs(obj - obj_ref) <= 1e-12 * max(obj_ref, 1e-300), (desc, obj, obj_ref)
         ref = oracle.solve_ex(Wf, N, M, tau, iters, add=Vf if use_add else None, add_scale=0.5, col_scale=cs,
                               square=square, tau_mode=int(rel), L=L, strict_paper=strict, cols_first=cols_first)
         S_ref = np.exp(ref["log_S"])
