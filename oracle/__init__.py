@@ -52,6 +52,8 @@ def _load():
         lib.tsenor_oracle_tau_eff.restype = dbl
         lib.tsenor_oracle_dykstra.argtypes = [p, i64, i64, i32, i32, dbl, i32, i32, p, p]
         lib.tsenor_oracle_dykstra.restype = i32
+        lib.tsenor_oracle_dykstra_adaptive.argtypes = [p, i64, i64, i32, i32, dbl, i32, i32, dbl, i32, p, p]
+        lib.tsenor_oracle_dykstra_adaptive.restype = i32
         lib.tsenor_oracle_round.argtypes = [p, p, i64, i64, i32, i32, i32, i32, p, p]
         lib.tsenor_oracle_round.restype = i32
         lib.tsenor_oracle_swap_scores.argtypes = [p, p, i32, i32, i32, p]
@@ -159,6 +161,25 @@ def dykstra(imp, N: int, M: int, tau_eff_value: float, T: int, cols_first: bool 
     if rc:
         raise ValueError(f"tsenor_oracle_dykstra failed: {rc}")
     return (log_S, log_Q) if return_log_Q else log_S
+
+
+ADAPTIVE_CHECK_EVERY = 4
+
+
+def dykstra_adaptive(imp, N: int, M: int, tau_eff_value: float, T: int, tol: float, cols_first: bool = False,
+                     check_every: int = ADAPTIVE_CHECK_EVERY):
+    """Algorithm 1 with T read as a bound: a block stops after a `check_every`-th iteration in which every row
+    and column scaling factor was within `tol` of 1.  Returns (log S, iterations done per block)."""
+    imp = _f32(imp)
+    rows, cols = imp.shape
+    log_S = np.empty((rows, cols), dtype=np.float64)
+    done = np.zeros((rows // M) * (cols // M), dtype=np.int32)
+    rc = _load().tsenor_oracle_dykstra_adaptive(_ptr(imp), rows, cols, N, M, float(tau_eff_value), T,
+                                                int(cols_first), float(tol), int(check_every), _ptr(log_S),
+                                                _ptr(done))
+    if rc:
+        raise ValueError(f"tsenor_oracle_dykstra_adaptive failed: {rc}")
+    return log_S, done
 
 
 def round_plan(key, imp, N: int, M: int, L: int = 10, strict_paper: bool = False):

@@ -134,6 +134,78 @@ static void dykstra_block(const float* imp, int64_t ld, int N, int M, double tau
   }
 }
 
+/* Algorithm 1 with an early exit ("maximum iterations T" read as a bound): after every `check_every`-th
+ * iteration the block stops if every scaling factor that iteration applied - N / (row sum) in the projection
+ * onto C1, N / (column sum) in the projection onto C2 - lies within `tol` of 1.  Returns the number of
+ * iterations done.  tol <= 0 never stops early. */
+static int dykstra_block_adaptive(const float* imp, int64_t ld, int N, int M, double tau_eff, int T,
+                                  int cols_first, double tol, int check_every, double* log_S, double* log_Q) {
+  const double logN = log((double)N);
+  for (int i = 0; i < M; ++i)
+    for (int j = 0; j < M; ++j) {
+      log_S[i * M + j] = tau_eff * (double)imp[i * ld + j];
+      log_Q[i * M + j] = 0.0;
+    }
+  for (int t = 0; t < T; ++t) {
+    double worst = 0.0; /* largest |factor - 1| of this iteration */
+    for (int pass = 0; pass < 2; ++pass) {
+      int do_rows = (pass == 0) != (cols_first != 0);
+      for (int k = 0; k < M; ++k) {
+        double shift = (do_rows ? lse(log_S + k * M, M, 1) : lse(log_S + k, M, M)) - logN;
+        double dev = fabs(exp(-shift) - 1.0); /* the factor is N / sum = exp(-shift) */
+        if (dev > worst) worst = dev;
+        for (int l = 0; l < M; ++l) {
+          if (do_rows)
+            log_S[k * M + l] -= shift;
+          else
+            log_S[l * M + k] -= shift;
+        }
+      }
+    }
+    for (int k = 0; k < M * M; ++k) {
+      double tmp = log_S[k] + log_Q[k];
+      double capped = tmp < 0.0 ? tmp : 0.0;
+      log_Q[k] = tmp - capped;
+      log_S[k] = capped;
+    }
+    if (tol > 0.0 && (t + 1) % check_every == 0 && worst <= tol) return t + 1;
+  }
+  return T;
+}
+
+/* The early-exit variant over every block.  iters_done (optional): one int per block, block-row major. */
+int tsenor_oracle_dykstra_adaptive(const float* imp, int64_t rows, int64_t cols, int N, int M, double tau_eff,
+                                   int T, int cols_first, double tol, int check_every, double* log_S,
+                                   int32_t* iters_done) {
+  if (!imp || !log_S || M <= 0 || rows <= 0 || cols <= 0 || rows % M || cols % M || N < 1 || N > M || T < 0 ||
+      check_every < 1)
+    return -1;
+  const int64_t bc = cols / M, nb = (rows / M) * bc;
+  int err = 0;
+#pragma omp parallel
+  {
+    double* s = (double*)malloc(sizeof(double) * M * M);
+    double* q = (double*)malloc(sizeof(double) * M * M);
+    if (!s || !q) {
+#pragma omp atomic write
+      err = 1;
+    } else {
+#pragma omp for schedule(dynamic, 16)
+      for (int64_t b = 0; b < nb; ++b) {
+        int64_t r0 = (b / bc) * M, c0 = (b % bc) * M;
+        int done = dykstra_block_adaptive(imp + r0 * cols + c0, cols, N, M, tau_eff, T, cols_first, tol,
+                                          check_every, s, q);
+        if (iters_done) iters_done[b] = done;
+        for (int i = 0; i < M; ++i)
+          for (int j = 0; j < M; ++j) log_S[(r0 + i) * cols + c0 + j] = s[i * M + j];
+      }
+    }
+    free(s);
+    free(q);
+  }
+  return err ? -2 : 0;
+}
+
 /* Algorithm 1 over every block.  imp: rows x cols floats (row-major, dense).
  * log_S: rows x cols doubles in the matrix's own layout; log_Q may be NULL. */
 int tsenor_oracle_dykstra(const float* imp, int64_t rows, int64_t cols, int N, int M,

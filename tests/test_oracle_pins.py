@@ -481,3 +481,37 @@ def test_simple_rounding_arm():
     # a key whose N largest entries per row already form a transposable pattern is returned as that pattern
     perm = np.kron(np.eye(2), np.ones((2, 2)))
     assert np.array_equal(oracle.simple_round(perm + 0.01 * rng.random((4, 4)), 2, 4), perm.astype(np.uint8))
+
+
+def test_early_exit_variant_of_algorithm1():
+    # "maximum iterations" read as a bound.  Pins: tol = 0 is the fixed-T result bit for bit; the count is a
+    # multiple of the check interval (or T); a looser tolerance never needs more iterations; the stopped state
+    # equals the fixed-T state at that count; its marginals are within the tolerance; a uniform block is a
+    # fixed point and stops at the first check.
+    rng = np.random.Generator(np.random.Philox(9090))
+    N, M, T = 4, 8, 400
+    imp = np.abs(rng.standard_normal((2 * M, 3 * M))).astype(np.float32)
+    te = oracle.tau_eff(imp, 0.02, oracle.TAU_REL_MATRIX_MAX)
+    fixed = oracle.dykstra(imp, N, M, te, T)
+    same, done0 = oracle.dykstra_adaptive(imp, N, M, te, T, 0.0)
+    assert np.array_equal(same, fixed) and np.all(done0 == T)
+    prev = None
+    for tol in (1e-2, 1e-4, 1e-6):
+        log_S, done = oracle.dykstra_adaptive(imp, N, M, te, T, tol)
+        assert np.all((done % oracle.ADAPTIVE_CHECK_EVERY == 0) | (done == T))
+        if prev is not None:
+            assert np.all(done >= prev)
+        prev = done
+        for b, (blk, n) in enumerate(zip(exact.blocks(log_S, M), done)):
+            r0, c0 = (b // 3) * M, (b % 3) * M
+            ref = oracle.dykstra(imp[r0:r0 + M, c0:c0 + M], N, M, te, int(n))
+            assert np.array_equal(blk, ref)
+            if n < T:
+                S = np.exp(blk)
+                assert np.abs(S.sum(axis=0) - N).max() <= 2 * tol * N and np.abs(S.sum(axis=1) - N).max() <= 2 * tol * N
+        assert (done < T).any()
+    flat = np.full((M, M), 0.7, dtype=np.float32)
+    _, done = oracle.dykstra_adaptive(flat, N, M, 1.0, 100, 1e-12)
+    assert done[0] == oracle.ADAPTIVE_CHECK_EVERY
+    _, done = oracle.dykstra_adaptive(flat, N, M, 1.0, 100, 1e-12, check_every=7)
+    assert done[0] == 7
