@@ -101,6 +101,9 @@ def main() -> int:
     ap.add_argument("--rows", type=int, default=0, help="override rows (debug)")
     ap.add_argument("--cols", type=int, default=0, help="override cols (debug)")
     ap.add_argument("--iters", type=int, default=-1, help="override the iteration count T (debug)")
+    ap.add_argument("--tol", type=float, default=0.0,
+                    help="early exit of the iterations (tsenor_problem.tol); not the headline configuration, the "
+                         "CPU baseline and the fp32 mode are skipped with it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096,
                     help="rows of the matrix the CPU oracle is timed on (default: the whole headline matrix, ~10 s)")
@@ -142,8 +145,12 @@ def main() -> int:
     mask = torch.empty(W.shape, dtype=torch.uint8, device=dev)
     stats = torch.zeros(4, dtype=torch.int64, device=dev)
     flags = binding.TSENOR_FLAG_FP32_ITERATIONS if args.fp32_iterations else 0
+    iters_done = None
+    if args.tol > 0.0:
+        args.no_cpu_baseline = args.no_fp32_mode = True
+        iters_done = torch.zeros((w.rows // w.M) * (w.cols // w.M), dtype=torch.int32, device=dev)
     prob = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask, col_scale=cs, tau_mode=w.tau_mode,
-                                flags=flags, stats_out=stats)
+                                flags=flags, stats_out=stats, tol=args.tol, iters_done_out=iters_done)
     work = torch.empty(binding.tsenor_workspace_bytes([prob]), dtype=torch.uint8, device=dev)
 
     if args.calibrate_copy:
@@ -211,6 +218,29 @@ def main() -> int:
             "blocks_identical_to_default_mode": round(1.0 - float(diff.float().mean()), 6),
         }
         del mask32
+
+    early_exit = None
+    if not args.fp32_iterations and not args.no_fp32_mode and args.tol == 0.0:
+        # the optional early exit (iteration count as a bound) on the same input, reported beside the headline
+        tol = 1e-5
+        mask_e = torch.empty_like(mask)
+        done_e = torch.zeros((w.rows // w.M) * (w.cols // w.M), dtype=torch.int32, device=dev)
+        prob_e = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask_e, col_scale=cs, tau_mode=w.tau_mode,
+                                      tol=tol, iters_done_out=done_e)
+        for _ in range(args.warmup):
+            binding.tsenor_mask_ex(prob_e, work)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        stage_e = binding.tsenor_mask_ex_profile(prob_e, work, args.steps)
+        torch.cuda.synchronize()
+        ms_e = (time.perf_counter() - t0) * 1e3 / args.steps
+        diff = (mask_e != mask).view(w.rows // w.M, w.M, w.cols // w.M, w.M).any(dim=3).any(dim=1)
+        early_exit = {
+            "tol": tol, "dtype": "f64", "value": round(weights / (ms_e * 1e-3), 1), "ms_per_step": round(ms_e, 4),
+            "kernel_ms": round(stage_e[1], 4), "mean_iterations": round(float(done_e.float().mean()), 1),
+            "blocks_identical_to_default_mode": round(1.0 - float(diff.float().mean()), 6),
+        }
+        del mask_e, done_e
     stats_host = stats.cpu().numpy().tolist()
 
     cpu_baseline = None
@@ -241,8 +271,11 @@ def main() -> int:
         "vs_baseline": None, "dtype": "f32" if args.fp32_iterations else "f64", "data": "synthetic",
         "config": {"workload": w.name, "rows": w.rows, "cols": w.cols, "N": w.N, "M": w.M, "iters": w.iters,
                    "tau": w.tau, "tau_mode": "rel_matrix_max" if w.tau_mode else "absolute",
-                   "storage": w.dtype, "importance": w.dist, "rounding_stats": stats_host},
+                   "storage": w.dtype, "importance": w.dist, "rounding_stats": stats_host,
+                   **({"tol": args.tol, "mean_iterations": round(float(iters_done.float().mean()), 1)}
+                      if iters_done is not None else {})},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "fp32_iterations_mode": other_mode,
+        "early_exit_mode": early_exit,
     }
     print(json.dumps(out), flush=True)
     return 0

@@ -143,7 +143,15 @@ typedef struct tsenor_problem {
   const uint8_t* prev_mask; /* device, optional, rows x cols bytes (0/1): the safeguard of App. A.1 (Assumption 1).
                              If this mask scores strictly higher than the one just found, under the importance of
                              THIS call, it is returned instead (mask, packed_out, pruned_out follow it) */
+  double tol;             /* 0 (default): exactly `iters` iterations, as Algorithm 1 is run in the paper's tables.
+                             > 0: `iters` is a bound ("maximum iterations"): a block stops after a
+                             TSENOR_ADAPTIVE_CHECK_EVERY-th iteration in which every row and column scaling factor
+                             (N / row sum, N / column sum) was within tol of 1.  Changes the result by O(tol).
+                             Double-precision iterations only (not with TSENOR_FLAG_FP32_ITERATIONS). */
+  int32_t* iters_done_out; /* device, optional, one int per block (block-row major): iterations that block ran */
 } tsenor_problem;
+
+enum { TSENOR_ADAPTIVE_CHECK_EVERY = 4 };
 
 enum { TSENOR_IMPORTANCE_ABS = 0, TSENOR_IMPORTANCE_SQUARE = 1 };
 

@@ -37,6 +37,7 @@ TSENOR_FLAG_GREEDY_M_LANES = 1 << 4
 TSENOR_FLAG_TILES_LARGE = 1 << 5
 TSENOR_FLAG_TILES_SMALL = 1 << 6
 TSENOR_FLAG_SIMPLE_ROUNDING = 1 << 7
+TSENOR_ADAPTIVE_CHECK_EVERY = 4
 TSENOR_IMPORTANCE_ABS = 0
 TSENOR_IMPORTANCE_SQUARE = 1
 
@@ -72,6 +73,8 @@ class tsenor_problem(ctypes.Structure):
         ("pruned_out", ctypes.c_void_p),
         ("objective_out", ctypes.c_void_p),
         ("prev_mask", ctypes.c_void_p),
+        ("tol", ctypes.c_double),
+        ("iters_done_out", ctypes.c_void_p),
     ]
 
 
@@ -139,7 +142,7 @@ def _dtype_code(W) -> int:
 def make_problem(W, N, M, tau, iters, *, mask, col_scale=None, tau_mode=TSENOR_TAU_ABSOLUTE,
                  local_search_steps=10, flags=0, plan_out=None, tau_eff_out=None, stats_out=None, add=None,
                  add_scale=0.0, importance=TSENOR_IMPORTANCE_ABS, packed_out=None, pruned_out=None,
-                 objective_out=None, prev_mask=None) -> tsenor_problem:
+                 objective_out=None, prev_mask=None, tol=0.0, iters_done_out=None) -> tsenor_problem:
     """Fill a tsenor_problem from device tensors (no copies; the tensors must outlive the call)."""
     if W.dim() != 2 or W.stride(1) != 1:
         raise ValueError("W must be a 2-D tensor with unit column stride")
@@ -168,6 +171,8 @@ def make_problem(W, N, M, tau, iters, *, mask, col_scale=None, tau_mode=TSENOR_T
     p.pruned_out = None if pruned_out is None else pruned_out.data_ptr()
     p.objective_out = None if objective_out is None else objective_out.data_ptr()
     p.prev_mask = None if prev_mask is None else prev_mask.data_ptr()
+    p.tol = float(tol)
+    p.iters_done_out = None if iters_done_out is None else iters_done_out.data_ptr()
     return p
 
 
@@ -225,7 +230,7 @@ def tsenor_mask(W, N, M, tau, iters, mask=None, stream=None):
 def solve(W, N, M, tau, iters, *, col_scale=None, tau_mode=TSENOR_TAU_ABSOLUTE, local_search_steps=10, flags=0,
           want_plan=False, want_stats=False, workspace=None, stream=None, add=None, add_scale=0.0,
           importance=TSENOR_IMPORTANCE_ABS, want_packed=False, want_pruned=False, want_objective=False,
-          prev_mask=None):
+          prev_mask=None, tol=0.0, want_iters_done=False):
     """Allocate outputs and scratch with torch, call tsenor_mask_ex once, return dict(mask[, plan, stats, tau_eff])."""
     import torch
 
@@ -237,10 +242,13 @@ def solve(W, N, M, tau, iters, *, col_scale=None, tau_mode=TSENOR_TAU_ABSOLUTE, 
     packed = torch.empty((W.shape[0], W.shape[1] // 8), dtype=torch.uint8, device=dev) if want_packed else None
     pruned = torch.empty(W.shape, dtype=W.dtype, device=dev) if want_pruned else None
     objective = torch.zeros(2, dtype=torch.float64, device=dev) if want_objective else None
+    iters_done = (torch.zeros((W.shape[0] // M) * (W.shape[1] // M), dtype=torch.int32, device=dev)
+                  if want_iters_done else None)
     p = make_problem(W, N, M, tau, iters, mask=mask, col_scale=col_scale, tau_mode=tau_mode,
                      local_search_steps=local_search_steps, flags=flags, plan_out=plan, tau_eff_out=tau_eff,
                      stats_out=stats, add=add, add_scale=add_scale, importance=importance, packed_out=packed,
-                     pruned_out=pruned, objective_out=objective, prev_mask=prev_mask)
+                     pruned_out=pruned, objective_out=objective, prev_mask=prev_mask, tol=tol,
+                     iters_done_out=iters_done)
     need = tsenor_workspace_bytes([p])
     if need == 0:
         # invalid arguments: let the entry point name the reason
@@ -259,4 +267,6 @@ def solve(W, N, M, tau, iters, *, col_scale=None, tau_mode=TSENOR_TAU_ABSOLUTE, 
         out["pruned"] = pruned
     if want_objective:
         out["objective"] = objective
+    if want_iters_done:
+        out["iters_done"] = iters_done
     return out

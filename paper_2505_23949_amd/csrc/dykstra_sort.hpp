@@ -213,9 +213,12 @@ __device__ __forceinline__ int reg_xor_y(int q) {
 // keeps the capped entries of the row pass for the column pass; otherwise they are recomputed from an
 // opaque copy of V (for tiles too large to hold twice: without the copy the compiler keeps the row pass's
 // values alive and spills them).
-template <class T, bool STORE, bool LDS_GATHER = false, class real, int TH, int TW, int OR>
-__device__ __forceinline__ void dykstra_iteration(real (&kap)[TH][TW], real (&Uown)[OR], real (&V)[TW], real Nd,
-                                                  real floor_, real* xr = nullptr, int rx = 0) {
+// ADAPT (early exit): `frozen` lanes apply factors of exactly 1 (their block has stopped; its state no longer
+// changes), and the largest |factor - 1| among the rows and columns this lane owns is returned.
+template <class T, bool STORE, bool LDS_GATHER = false, bool ADAPT = false, class real, int TH, int TW, int OR>
+__device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uown)[OR], real (&V)[TW], real Nd,
+                                                  real floor_, real* xr = nullptr, int rx = 0, bool frozen = false) {
+  real worst = 0;
   constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
   static_assert(OR == OWN_R, "one scaling per owned row");
   real e[STORE ? TH : 1][STORE ? TW : 1];
@@ -236,6 +239,10 @@ __device__ __forceinline__ void dykstra_iteration(real (&kap)[TH][TW], real (&Uo
 #pragma unroll
   for (int a = 0; a < OWN_R; ++a) {
     R[a] = Nd * fast_rcp(vmax(R[a], floor_));
+    if constexpr (ADAPT) {
+      worst = vmax(worst, fabs(R[a] - real(1)));
+      R[a] = frozen ? real(1) : R[a];
+    }
     Uown[a] *= R[a];
   }
   if constexpr (LDS_GATHER) {
@@ -274,7 +281,13 @@ __device__ __forceinline__ void dykstra_iteration(real (&kap)[TH][TW], real (&Uo
   }
   reduce_scatter_y<T, real, TW>(C);
 #pragma unroll
-  for (int b = 0; b < OWN_C; ++b) C[b] = Nd * fast_rcp(vmax(C[b], floor_));
+  for (int b = 0; b < OWN_C; ++b) {
+    C[b] = Nd * fast_rcp(vmax(C[b], floor_));
+    if constexpr (ADAPT) {
+      worst = vmax(worst, fabs(C[b] - real(1)));
+      C[b] = frozen ? real(1) : C[b];
+    }
+  }
   all_gather_y<T, real, TW>(C);
 #pragma unroll
   for (int a = 0; a < TH; ++a)
@@ -283,6 +296,7 @@ __device__ __forceinline__ void dykstra_iteration(real (&kap)[TH][TW], real (&Uo
 #pragma unroll
   for (int b = 0; b < TW; ++b) V[b] *= C[b];
   // lines 5-6 (cap and dual update) are the clamp at the top of the next pass
+  return worst;
 }
 
 // min of two floats as the bare instruction.  fminf() makes the compiler quiet possible signalling NaNs in
@@ -410,9 +424,11 @@ __device__ __forceinline__ void sort_ascending(double (&c)[E], int q) {
   }
 }
 
-template <int M, bool FAST>
+template <int M, bool FAST, bool ADAPT = false>
 struct DykstraLaunch {
-  static constexpr int kWavesPerGroup = 4;
+  // with the early exit the waves of a launch run for very different times; one-wave workgroups let the
+  // dispatcher refill every wave slot as it frees (a four-wave workgroup holds its slots until its slowest wave)
+  static constexpr int kWavesPerGroup = ADAPT ? 1 : 4;
   static constexpr int kThreads = kWavesPerGroup * kWave;
   // waves per SIMD the register budget is set for.  The fp32 loop wants more than two (one wave issues at
   // most every ~5 cycles, an fp32 instruction occupies the SIMD for 2); its state fits 128 registers, but at
@@ -423,8 +439,8 @@ struct DykstraLaunch {
 
 // ZERO_T: the instantiation for T = 0 (no iterations, keys are K itself).  It is a template parameter
 // rather than a branch because keeping both paths in one kernel costs the iterating path ~40 registers.
-template <int M, bool FAST, bool ZERO_T = false, bool SMALL = false>
-__global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<M, FAST>::kWavesPerSimd)) void dykstra_sort_kernel(
+template <int M, bool FAST, bool ZERO_T = false, bool SMALL = false, bool ADAPT = false>
+__global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (DykstraLaunch<M, FAST, ADAPT>::kWavesPerSimd)) void dykstra_sort_kernel(
     Batch batch) {
   using T = Tiling<M, SMALL>;
   const int which = find_problem(batch, blockIdx.x);
@@ -435,7 +451,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
   double* tau_eff_out = batch.e[which].tau_eff_out;
   const unsigned int group = blockIdx.x - batch.first[which];  // workgroup index within the matrix
   constexpr int GX = 1 << T::NX, GY = 1 << T::NY, TH = M / GY, TW = M / GX, LPB = GX * GY, BPW = kWave / LPB,
-                E = TH * TW, SHX = ilog2(TH) - T::NX, WPG = DykstraLaunch<M, FAST>::kWavesPerGroup;
+                E = TH * TW, SHX = ilog2(TH) - T::NX, WPG = DykstraLaunch<M, FAST, ADAPT>::kWavesPerGroup;
   const int lane = threadIdx.x & (kWave - 1), wave_in_group = threadIdx.x / kWave;
   const int64_t wave = (int64_t)group * WPG + wave_in_group;
   const int q = lane % LPB, gx = q % GX, gy = q / GX;
@@ -499,6 +515,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
   all_reduce_max_x<T, TH>(mrow);
 
   double c[E];  // sort keys
+  int iters_done = 0;
   if constexpr (ZERO_T) {
     // no iterations: the greedy order is descending K itself
     const int rx0 = fresh(rx), ry0 = fresh(ry);
@@ -526,6 +543,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
       }
 
     const double Nd = (double)p.N;
+    iters_done = p.T;
     // logs of the scalings of the rows and columns this lane owns (the first registers after a
     // reduce-scatter); the other lanes of the lane-row / lane-column hold the same values for theirs
     constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
@@ -541,15 +559,31 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
         const int t_double = p.T < kWarmIters ? p.T : kWarmIters;
         for (int t = 0; t < t_double; ++t) dykstra_iteration<T, false>(kap, Uown, V, Nd, 1e-300);
       } else {
-        if constexpr ((M == 32 || M == 64) && !SMALL) {
-          // the row scalings of an iteration are gathered through LDS (measured 1.2 % faster than DPP moves;
-          // doing the same for the column scalings as well exposed a second LDS round trip and gained nothing):
-          // lane-row r of the wave keeps its 8 row scalings at xrows[wave][r][0..8)
-          __shared__ double xrows[WPG][kWave / 8][8];
-          double* xr = &xrows[wave_in_group][lane / 8][0];
-          for (int t = 0; t < p.T; ++t) dykstra_iteration<T, T::STORE_E, true>(kap, Uown, V, Nd, 1e-300, xr, rx);
+        // In the 32- and 64-wide kernels the row scalings of an iteration are gathered through LDS (measured
+        // ~1 % faster than DPP moves; doing the same for the column scalings as well exposed a second LDS round
+        // trip and gained nothing): lane-row r of the wave keeps its 8 row scalings at xrows[wave][r][0..8)
+        constexpr bool kLdsGather = (M == 32 || M == 64) && !SMALL;
+        __shared__ double xrows[kLdsGather ? WPG : 1][kLdsGather ? kWave / 8 : 1][8];
+        double* xr = kLdsGather ? &xrows[wave_in_group][lane / 8][0] : nullptr;
+        if constexpr (ADAPT) {
+          // iteration count as a bound: every TSENOR_ADAPTIVE_CHECK_EVERY-th iteration the largest |factor - 1|
+          // of the block is compared with the tolerance; a block that passes is frozen, the wave leaves when
+          // all its blocks are
+          bool frozen = false;
+          for (int t = 0; t < p.T; ++t) {
+            double worst =
+                dykstra_iteration<T, T::STORE_E, kLdsGather, true>(kap, Uown, V, Nd, 1e-300, xr, rx, frozen);
+            if ((t + 1) % TSENOR_ADAPTIVE_CHECK_EVERY == 0) {
+              worst = block_max<LPB>(worst);
+              if (!frozen && worst <= p.tol) {
+                frozen = true;
+                iters_done = t + 1;
+              }
+              if (__all(frozen)) break;
+            }
+          }
         } else {
-          for (int t = 0; t < p.T; ++t) dykstra_iteration<T, T::STORE_E>(kap, Uown, V, Nd, 1e-300);
+          for (int t = 0; t < p.T; ++t) dykstra_iteration<T, T::STORE_E, kLdsGather>(kap, Uown, V, Nd, 1e-300, xr, rx);
         }
       }
 #pragma unroll
@@ -676,6 +710,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST>::kThreads), (DykstraLaunch<
 
   sort_ascending<E, LPB>(c, q);
 
+  if (active && q == 0 && batch.e[which].iters_done_out) batch.e[which].iters_done_out[blk] = iters_done;
   if (active) {
     unsigned short* dst = order + blk * (int64_t)(M * M) + q * E;
 #pragma unroll

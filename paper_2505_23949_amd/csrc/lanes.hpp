@@ -55,4 +55,15 @@ __device__ __forceinline__ float lane_xor(float v) {
   return __int_as_float(lane_xor_i32<MASK>(__float_as_int(v)));
 }
 
+// max over the LPB consecutive lanes that hold a block (LPB a power of two)
+template <int LPB, int STEP = 1>
+__device__ __forceinline__ double block_max(double v) {
+  if constexpr (STEP < LPB) {
+    v = fmax(v, lane_xor<STEP>(v));
+    return block_max<LPB, STEP * 2>(v);
+  } else {
+    return v;
+  }
+}
+
 }  // namespace tsenor_dev

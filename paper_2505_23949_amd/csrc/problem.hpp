@@ -27,6 +27,7 @@ struct DevProblem {
   int tau_mode;
   float add_scale;
   int square;
+  double tol;  // > 0: early exit of the iterations (see tsenor_problem.tol)
 };
 
 // One fused launch serves up to kMaxBatch matrices that share M and the kernel variant: every kernel gets the
@@ -49,6 +50,7 @@ struct BatchEntry {
   void* pruned_out;
   double* objective_out;
   const uint8_t* prev_mask;
+  int* iters_done_out;
   int wide_store;               // mask rows can be written with 16-byte stores
   int absmax_vec;               // rows can be read with 16-byte loads by the maximum pre-pass
 };

@@ -170,7 +170,9 @@ int validate(const tsenor_problem* p) {
   if (p->importance != TSENOR_IMPORTANCE_ABS && p->importance != TSENOR_IMPORTANCE_SQUARE) return TSENOR_ERR_UNSUPPORTED;
   if (p->add && !std::isfinite(p->add_scale)) return TSENOR_ERR_PARAM;
   if ((p->packed_out || p->pruned_out || p->prev_mask) && p->cols % 8) return TSENOR_ERR_SHAPE;
-  if ((p->N == 0 || p->N == p->M) && (p->objective_out || p->prev_mask)) return TSENOR_ERR_UNSUPPORTED;
+  if ((p->N == 0 || p->N == p->M) && (p->objective_out || p->prev_mask || p->iters_done_out)) return TSENOR_ERR_UNSUPPORTED;
+  if (!(p->tol >= 0.0) || !std::isfinite(p->tol)) return TSENOR_ERR_PARAM;
+  if (p->tol > 0.0 && (p->flags & TSENOR_FLAG_FP32_ITERATIONS)) return TSENOR_ERR_UNSUPPORTED;
   return TSENOR_OK;
 }
 
@@ -183,16 +185,17 @@ struct Variant {
   uint32_t greedy;  // 0: chosen by size, else the TSENOR_FLAG_GREEDY_* asked for
   uint32_t tiles;   // 0: chosen by size, else the TSENOR_FLAG_TILES_* asked for
   bool simple;      // TSENOR_FLAG_SIMPLE_ROUNDING
+  bool adaptive;    // tol > 0: the early-exit instantiation of the Dykstra kernel
   bool operator==(const Variant& o) const {
     return M == o.M && fast == o.fast && zero_t == o.zero_t && greedy == o.greedy && tiles == o.tiles &&
-           simple == o.simple;
+           simple == o.simple && adaptive == o.adaptive;
   }
 };
 inline Variant variant_of(const tsenor_problem& p) {
   return {p.M, p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0, p.iters == 0,
           p.flags & (uint32_t)(TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES),
           p.flags & (uint32_t)(TSENOR_FLAG_TILES_LARGE | TSENOR_FLAG_TILES_SMALL),
-          (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0};
+          (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0, p.tol > 0.0 && p.iters > 0};
 }
 
 // Below this many blocks in a launch the Dykstra kernel uses the small tiles (M = 16 and 32, double
@@ -233,6 +236,7 @@ BatchEntry entry_of(const tsenor_problem& p, char* ws) {
   }
   dp.tau = p.tau;
   dp.tau_mode = p.tau_mode;
+  dp.tol = p.tol;
   e.rows = p.rows;
   e.hdr = reinterpret_cast<WsHeader*>(ws + l.header);
   e.order = reinterpret_cast<unsigned short*>(ws + l.order);
@@ -246,6 +250,7 @@ BatchEntry entry_of(const tsenor_problem& p, char* ws) {
   e.pruned_out = p.pruned_out;
   e.objective_out = p.objective_out;
   e.prev_mask = p.prev_mask;
+  e.iters_done_out = p.iters_done_out;
   e.wide_store = reinterpret_cast<uintptr_t>(p.mask) % 16 == 0;
   const size_t esize = p.dtype == TSENOR_BF16 ? 2 : 4;
   e.absmax_vec = p.cols % 8 == 0 && reinterpret_cast<uintptr_t>(p.W) % 16 == 0 && ((size_t)p.ld * esize) % 16 == 0 &&
@@ -303,7 +308,7 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   int64_t total_blocks = 0;
   for (int k = 0; k < b.count; ++k) total_blocks += b.e[k].p.nblocks;
   constexpr bool kHasSmall = M == 16 || M == 32;
-  const bool small = kHasSmall && !v.fast && !v.zero_t &&
+  const bool small = kHasSmall && !v.fast && !v.zero_t && !v.adaptive &&
                      (v.tiles ? v.tiles == TSENOR_FLAG_TILES_SMALL : total_blocks < small_tiles_below_blocks(M));
   if (small) {
     if constexpr (kHasSmall) {
@@ -318,9 +323,13 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
     dykstra_sort_kernel<M, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
   } else {
     using L = DykstraLaunch<M, false>;
-    if (!assign_groups(b, blocks, (int64_t)BPW * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
+    using LA = DykstraLaunch<M, false, true>;
+    if (!assign_groups(b, blocks, (int64_t)BPW * (v.adaptive ? LA::kWavesPerGroup : L::kWavesPerGroup)))
+      return TSENOR_ERR_SHAPE;
     if (v.zero_t)
       dykstra_sort_kernel<M, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
+    else if (v.adaptive)
+      dykstra_sort_kernel<M, false, false, false, true><<<b.first[b.count], LA::kThreads, 0, stream>>>(b);
     else
       dykstra_sort_kernel<M, false><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
   }

@@ -361,6 +361,51 @@ def test_zero_blocks_outliers_and_zero_scales(dev, M, N):
             assert res["tau_eff"].cpu().numpy()[0] == ref["tau_eff"]
 
 
+@pytest.mark.parametrize("M,N,dtype,tol", [(32, 16, "bf16", 1e-3), (16, 8, "f32", 1e-2), (64, 32, "f32", 1e-4),
+                                           (8, 3, "f32", 1e-5), (4, 2, "f32", 1e-3)])
+def test_early_exit_of_the_iterations(dev, M, N, dtype, tol):
+    # iteration count as a bound (tsenor_problem.tol): per block the count must be the oracle's, and where it
+    # is, the plan and the mask must be the oracle's for that count; a count may differ by one check interval
+    # where the deviation sits within rounding of the tolerance
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.Workload(f"early_exit_{N}of{M}", 6 * M, 9 * M, N, M, 0.01, 600, dtype, "wanda", 7300 + M)
+    g = synth.generate(w)
+    W, cs = _to_device(g, w, dev)
+    for cols_first in (False, True):
+        print(f"[case] early exit {w.name} tol={tol} cols_first={cols_first}", flush=True)
+        res = binding.solve(W, N, M, w.tau, w.iters, col_scale=cs, tau_mode=w.tau_mode, tol=tol, want_plan=True,
+                            want_iters_done=True, flags=binding.TSENOR_FLAG_COLS_FIRST if cols_first else 0)
+        torch.cuda.synchronize()
+        imp = oracle.importance(g["W_f32"], g["col_scale"])
+        te = oracle.tau_eff(imp, w.tau, w.tau_mode)
+        assert float(res["tau_eff"].cpu()[0]) == te
+        log_S, done_ref = oracle.dykstra_adaptive(imp, N, M, te, w.iters, tol, cols_first=cols_first)
+        done = res["iters_done"].cpu().numpy()
+        agree = done == done_ref
+        assert agree.mean() >= 0.95, (done, done_ref)
+        assert np.all(np.abs(done - done_ref) <= binding.TSENOR_ADAPTIVE_CHECK_EVERY)
+        assert (done_ref < w.iters).any(), "the case should exercise the early exit"
+        plan_err = np.abs(exact.blocks(res["plan"].cpu().numpy(), M) - np.exp(exact.blocks(log_S, M))).max(axis=(1, 2))
+        assert plan_err[agree].max() <= PLAN_ATOL
+        assert plan_err.max() <= 10 * tol
+        mask_ref, _ = oracle.round_plan(log_S, imp, N, M)
+        mask = res["mask"].cpu().numpy()
+        assert exact.is_transposable_nm(mask, N, M)
+        same = (exact.blocks(mask, M) == exact.blocks(mask_ref, M)).all(axis=(1, 2))
+        assert same[agree].mean() >= 0.98
+    # tol = 0 and a tolerance no block reaches give the fixed-count result and the full count
+    fixed = binding.solve(W, N, M, w.tau, 40, col_scale=cs, tau_mode=w.tau_mode, want_plan=True, want_iters_done=True)
+    tight = binding.solve(W, N, M, w.tau, 40, col_scale=cs, tau_mode=w.tau_mode, want_plan=True, want_iters_done=True,
+                          tol=1e-300)
+    torch.cuda.synchronize()
+    assert torch.equal(fixed["mask"], tight["mask"])
+    assert np.abs(fixed["plan"].cpu().numpy() - tight["plan"].cpu().numpy()).max() <= 1e-12
+    assert int(fixed["iters_done"].min()) == 40 and int(tight["iters_done"].min()) == 40
+
+
 def test_zero_iterations_rounds_the_importance(dev):
     from dataclasses import replace
 
