@@ -21,10 +21,12 @@
  *     the optional plan use leading dimension `cols`.
  *   - rows and cols must be multiples of M (the method never pads, Sec. 3.1);
  *     M must be one of 4, 8, 16, 32, 64 and 0 <= N <= M.  N == 0 and N == M are
- *     answered with the all-zero / all-one mask without iterating (objective_out
- *     and prev_mask are TSENOR_ERR_UNSUPPORTED for them: there is nothing to compare).
+ *     answered with the all-zero / all-one mask without iterating (objective_out,
+ *     prev_mask and iters_done_out are TSENOR_ERR_UNSUPPORTED for them: there is
+ *     nothing to compare or count).
  *   - The arithmetic of the Dykstra iterations, the sort keys and the swap scores
- *     is IEEE double precision on the device.
+ *     is IEEE double precision on the device (iterations after the eighth in single
+ *     precision with TSENOR_FLAG_FP32_ITERATIONS).
  */
 #ifndef TSENOR_H
 #define TSENOR_H
