@@ -65,7 +65,7 @@ def bench_layer(args) -> int:
         mask = torch.empty(W.shape, dtype=torch.uint8, device=dev)
         flags = binding.TSENOR_FLAG_FP32_ITERATIONS if args.fp32_iterations else 0
         probs.append(binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask, col_scale=cs, tau_mode=w.tau_mode,
-                                          flags=flags))
+                                          flags=flags, tol=args.tol))
         keep += [W, cs, mask]
     work = torch.empty(binding.tsenor_workspace_bytes(probs), dtype=torch.uint8, device=dev)
     for _ in range(args.warmup):
@@ -85,7 +85,7 @@ def bench_layer(args) -> int:
         "data": "synthetic",
         "config": {"workload": "cfg4_layer", "matrices": [[w.rows, w.cols] for w in ws], "weights": weights,
                    "N": 16, "M": 32, "iters": 300, "tau": 0.005, "tau_mode": "rel_matrix_max", "storage": "f32",
-                   "importance": "wanda"},
+                   "importance": "wanda", **({"tol": args.tol} if args.tol > 0.0 else {})},
         "roofline": None, "cpu_baseline": None,
     }
     print(json.dumps(out), flush=True)
