@@ -219,28 +219,31 @@ def main() -> int:
         }
         del mask32
 
-    early_exit = None
+    early_exit = early_exit32 = None
     if not args.fp32_iterations and not args.no_fp32_mode and args.tol == 0.0:
-        # the optional early exit (iteration count as a bound) on the same input, reported beside the headline
-        tol = 1e-5
-        mask_e = torch.empty_like(mask)
-        done_e = torch.zeros((w.rows // w.M) * (w.cols // w.M), dtype=torch.int32, device=dev)
-        prob_e = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask_e, col_scale=cs, tau_mode=w.tau_mode,
-                                      tol=tol, iters_done_out=done_e)
-        for _ in range(args.warmup):
-            binding.tsenor_mask_ex(prob_e, work)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        stage_e = binding.tsenor_mask_ex_profile(prob_e, work, args.steps)
-        torch.cuda.synchronize()
-        ms_e = (time.perf_counter() - t0) * 1e3 / args.steps
-        diff = (mask_e != mask).view(w.rows // w.M, w.M, w.cols // w.M, w.M).any(dim=3).any(dim=1)
-        early_exit = {
-            "tol": tol, "dtype": "f64", "value": round(weights / (ms_e * 1e-3), 1), "ms_per_step": round(ms_e, 4),
-            "kernel_ms": round(stage_e[1], 4), "mean_iterations": round(float(done_e.float().mean()), 1),
-            "blocks_identical_to_default_mode": round(1.0 - float(diff.float().mean()), 6),
-        }
-        del mask_e, done_e
+        # the optional early exit (iteration count as a bound) on the same input, reported beside the headline:
+        # with double-precision iterations, and combined with the fp32-iteration mode
+        def early_exit_run(tol, extra_flags, dtype):
+            mask_e = torch.empty_like(mask)
+            done_e = torch.zeros((w.rows // w.M) * (w.cols // w.M), dtype=torch.int32, device=dev)
+            prob_e = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask_e, col_scale=cs,
+                                          tau_mode=w.tau_mode, tol=tol, iters_done_out=done_e, flags=extra_flags)
+            for _ in range(args.warmup):
+                binding.tsenor_mask_ex(prob_e, work)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            stage_e = binding.tsenor_mask_ex_profile(prob_e, work, args.steps)
+            torch.cuda.synchronize()
+            ms_e = (time.perf_counter() - t0) * 1e3 / args.steps
+            diff = (mask_e != mask).view(w.rows // w.M, w.M, w.cols // w.M, w.M).any(dim=3).any(dim=1)
+            return {
+                "tol": tol, "dtype": dtype, "value": round(weights / (ms_e * 1e-3), 1), "ms_per_step": round(ms_e, 4),
+                "kernel_ms": round(stage_e[1], 4), "mean_iterations": round(float(done_e.float().mean()), 1),
+                "blocks_identical_to_default_mode": round(1.0 - float(diff.float().mean()), 6),
+            }
+
+        early_exit = early_exit_run(1e-5, 0, "f64")
+        early_exit32 = early_exit_run(1e-5, binding.TSENOR_FLAG_FP32_ITERATIONS, "f32")
     stats_host = stats.cpu().numpy().tolist()
 
     cpu_baseline = None
@@ -275,7 +278,7 @@ def main() -> int:
                    **({"tol": args.tol, "mean_iterations": round(float(iters_done.float().mean()), 1)}
                       if iters_done is not None else {})},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "fp32_iterations_mode": other_mode,
-        "early_exit_mode": early_exit,
+        "early_exit_mode": early_exit, "early_exit_fp32_mode": early_exit32,
     }
     print(json.dumps(out), flush=True)
     return 0

@@ -149,7 +149,8 @@ typedef struct tsenor_problem {
                              > 0: `iters` is a bound ("maximum iterations"): a block stops after a
                              TSENOR_ADAPTIVE_CHECK_EVERY-th iteration in which every row and column scaling factor
                              (N / row sum, N / column sum) was within tol of 1.  Changes the result by O(tol).
-                             Double-precision iterations only (not with TSENOR_FLAG_FP32_ITERATIONS). */
+                             With TSENOR_FLAG_FP32_ITERATIONS the factors after the eighth iteration are
+                             single-precision numbers: a tol below ~1e-6 is then never met */
   int32_t* iters_done_out; /* device, optional, one int per block (block-row major): iterations that block ran */
 } tsenor_problem;
 

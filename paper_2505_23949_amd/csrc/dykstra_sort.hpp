@@ -314,10 +314,13 @@ __device__ __forceinline__ float raw_min(float a, float b) {
 //     sum_j e'_ij = (sum_j e_ij) / U_i,  so  U_i R_i = N / sum_j e'_ij   and   sum_i e_ij R_i = sum_i e'_ij (U_i R_i).
 // U, Uinv: scaling of every tile row and its reciprocal; V: scaling of every tile column.  A row scaling
 // grows by at most 2^10 per iteration (keeps everything finite on degenerate input).
-template <class T, bool LDS_GATHER = false, int TH, int TW>
-__device__ __forceinline__ void dykstra_iteration_f32(const float (&kap)[TH][TW], float (&U)[TH], float (&Uinv)[TH],
-                                                      float (&V)[TW], float Nf, float2* xr = nullptr, int rx = 0) {
+// ADAPT as in dykstra_iteration: the row factor of this form is Un_i / U_i.
+template <class T, bool LDS_GATHER = false, bool ADAPT = false, int TH, int TW>
+__device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW], float (&U)[TH], float (&Uinv)[TH],
+                                                       float (&V)[TW], float Nf, float2* xr = nullptr, int rx = 0,
+                                                       bool frozen = false) {
   constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
+  float worst = 0;
   float e[TH][TW], S[TH], C[TW];
 #pragma unroll
   for (int a = 0; a < TH; ++a) {
@@ -332,7 +335,13 @@ __device__ __forceinline__ void dykstra_iteration_f32(const float (&kap)[TH][TW]
 #pragma unroll
   for (int a = 0; a < OWN_R; ++a) {
     Un[a] = fminf(Nf * fast_rcp(S[a]), U[a] * 1024.0f);  // new scaling of an owned row
-    S[a] = fast_rcp(Un[a]);                              // and its reciprocal
+    if constexpr (ADAPT) {
+      worst = fmaxf(worst, fabsf(fmaf(Un[a], Uinv[a], -1.0f)));
+      Un[a] = frozen ? U[a] : Un[a];
+      S[a] = frozen ? Uinv[a] : fast_rcp(Un[a]);
+    } else {
+      S[a] = fast_rcp(Un[a]);  // and its reciprocal
+    }
   }
   if constexpr (LDS_GATHER) {
     // scaling and reciprocal of the owned row through LDS as one pair (see dykstra_iteration)
@@ -362,10 +371,17 @@ __device__ __forceinline__ void dykstra_iteration_f32(const float (&kap)[TH][TW]
   }
   reduce_scatter_y<T, float, TW>(C);
 #pragma unroll
-  for (int b = 0; b < OWN_C; ++b) C[b] = Nf * fast_rcp(fmaxf(C[b], Nf * 0x1p-10f));
+  for (int b = 0; b < OWN_C; ++b) {
+    C[b] = Nf * fast_rcp(fmaxf(C[b], Nf * 0x1p-10f));
+    if constexpr (ADAPT) {
+      worst = fmaxf(worst, fabsf(C[b] - 1.0f));
+      C[b] = frozen ? 1.0f : C[b];
+    }
+  }
   all_gather_y<T, float, TW>(C);
 #pragma unroll
   for (int b = 0; b < TW; ++b) V[b] *= C[b];
+  return worst;
 }
 
 __device__ __forceinline__ void compare_exchange(double& lo, double& hi) {
@@ -548,6 +564,14 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
     // reduce-scatter); the other lanes of the lane-row / lane-column hold the same values for theirs
     constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
     double lu_own[OWN_R], lv_own[OWN_C];
+    // early exit: a block whose factors have passed the tolerance is frozen at that iteration
+    bool frozen = false;
+    auto freeze_if = [&](bool passed, int t_done) {
+      if (!frozen && passed) {
+        frozen = true;
+        iters_done = t_done;
+      }
+    };
     {
       double Uown[OWN_R], V[TW];
 #pragma unroll
@@ -557,7 +581,12 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
       if constexpr (FAST) {
         // the entries are recomputed in the column pass: this phase must fit the registers of the fp32 loop
         const int t_double = p.T < kWarmIters ? p.T : kWarmIters;
-        for (int t = 0; t < t_double; ++t) dykstra_iteration<T, false>(kap, Uown, V, Nd, 1e-300);
+        for (int t = 0; t < t_double; ++t) {
+          double worst = dykstra_iteration<T, false, false, ADAPT>(kap, Uown, V, Nd, 1e-300, (double*)nullptr, 0, frozen);
+          if constexpr (ADAPT) {
+            if ((t + 1) % TSENOR_ADAPTIVE_CHECK_EVERY == 0) freeze_if(block_max<LPB>(worst) <= p.tol, t + 1);
+          }
+        }
       } else {
         // In the 32- and 64-wide kernels the row scalings of an iteration are gathered through LDS (measured
         // ~1 % faster than DPP moves; doing the same for the column scalings as well exposed a second LDS round
@@ -569,16 +598,11 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
           // iteration count as a bound: every TSENOR_ADAPTIVE_CHECK_EVERY-th iteration the largest |factor - 1|
           // of the block is compared with the tolerance; a block that passes is frozen, the wave leaves when
           // all its blocks are
-          bool frozen = false;
           for (int t = 0; t < p.T; ++t) {
             double worst =
                 dykstra_iteration<T, T::STORE_E, kLdsGather, true>(kap, Uown, V, Nd, 1e-300, xr, rx, frozen);
             if ((t + 1) % TSENOR_ADAPTIVE_CHECK_EVERY == 0) {
-              worst = block_max<LPB>(worst);
-              if (!frozen && worst <= p.tol) {
-                frozen = true;
-                iters_done = t + 1;
-              }
+              freeze_if(block_max<LPB>(worst) <= p.tol, t + 1);
               if (__all(frozen)) break;
             }
           }
@@ -599,7 +623,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
     }
 
     if constexpr (FAST) {
-      if (p.T > kWarmIters) {
+      if (p.T > kWarmIters && !(ADAPT && __all(frozen))) {
         // fp32 phase: kap32 = fl32(kap U V) for the double scalings U V reached so far, and fp32 scalings
         // U32, V32 relative to them.  kap is not kept: a rebuild reloads the importance.
         float kap32[TH][TW], U32[TH], Uinv32[TH], V32[TW];
@@ -649,14 +673,23 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
           }
         };
         rebuild();
-        for (int t = kWarmIters; t < p.T;) {
+        bool all_frozen = false;
+        for (int t = kWarmIters; t < p.T && !all_frozen;) {
           const int stop = (p.T - t > kChunk) ? t + kChunk : p.T;
-          if constexpr (M == 32 || M == 64) {
-            __shared__ float2 xrows32[WPG][kWave / 8][8];
-            float2* xr = &xrows32[wave_in_group][lane / 8][0];
-            for (; t < stop; ++t) dykstra_iteration_f32<T, true>(kap32, U32, Uinv32, V32, Nf, xr, rx);
+          constexpr bool kLdsGather32 = M == 32 || M == 64;
+          __shared__ float2 xrows32[kLdsGather32 ? WPG : 1][kLdsGather32 ? kWave / 8 : 1][8];
+          float2* xr = kLdsGather32 ? &xrows32[wave_in_group][lane / 8][0] : nullptr;
+          if constexpr (ADAPT) {
+            for (; t < stop && !all_frozen; ++t) {
+              const float worst =
+                  dykstra_iteration_f32<T, kLdsGather32, true>(kap32, U32, Uinv32, V32, Nf, xr, rx, frozen);
+              if ((t + 1) % TSENOR_ADAPTIVE_CHECK_EVERY == 0) {
+                freeze_if(block_max<LPB>((double)worst) <= p.tol, t + 1);
+                all_frozen = __all(frozen);
+              }
+            }
           } else {
-            for (; t < stop; ++t) dykstra_iteration_f32<T>(kap32, U32, Uinv32, V32, Nf);
+            for (; t < stop; ++t) dykstra_iteration_f32<T, kLdsGather32>(kap32, U32, Uinv32, V32, Nf, xr, rx);
           }
           float mxs = U32[0], mns = U32[0];
 #pragma unroll

@@ -172,7 +172,6 @@ int validate(const tsenor_problem* p) {
   if ((p->packed_out || p->pruned_out || p->prev_mask) && p->cols % 8) return TSENOR_ERR_SHAPE;
   if ((p->N == 0 || p->N == p->M) && (p->objective_out || p->prev_mask || p->iters_done_out)) return TSENOR_ERR_UNSUPPORTED;
   if (!(p->tol >= 0.0) || !std::isfinite(p->tol)) return TSENOR_ERR_PARAM;
-  if (p->tol > 0.0 && (p->flags & TSENOR_FLAG_FP32_ITERATIONS)) return TSENOR_ERR_UNSUPPORTED;
   return TSENOR_OK;
 }
 
@@ -317,6 +316,10 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
       if (!assign_groups(b, blocks, (int64_t)BPWS * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
       dykstra_sort_kernel<M, false, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
     }
+  } else if (v.fast && v.adaptive) {
+    using L = DykstraLaunch<M, true, true>;
+    if (!assign_groups(b, blocks, (int64_t)BPW * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
+    dykstra_sort_kernel<M, true, false, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
   } else if (v.fast) {
     using L = DykstraLaunch<M, true>;
     if (!assign_groups(b, blocks, (int64_t)BPW * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;

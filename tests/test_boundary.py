@@ -178,7 +178,7 @@ def test_validation_of_the_extended_fields(lib):
     assert call(_problem(flags=b.TSENOR_FLAG_TILES_SMALL)) == b.TSENOR_ERR_WORKSPACE
     assert call(_problem(tol=-1.0)) == b.TSENOR_ERR_PARAM
     assert call(_problem(tol=float("nan"))) == b.TSENOR_ERR_PARAM
-    assert call(_problem(tol=1e-3, flags=b.TSENOR_FLAG_FP32_ITERATIONS)) == b.TSENOR_ERR_UNSUPPORTED
+    assert call(_problem(tol=1e-3, flags=b.TSENOR_FLAG_FP32_ITERATIONS)) == b.TSENOR_ERR_WORKSPACE
     assert call(_problem(tol=1e-3)) == b.TSENOR_ERR_WORKSPACE
     assert call(_problem(N=0, iters_done_out=0x4000)) == b.TSENOR_ERR_UNSUPPORTED
     assert call(_problem(add=0x3000, add_scale=float("inf"))) == b.TSENOR_ERR_PARAM
