@@ -89,6 +89,18 @@ struct Tiling<64, false> {
   static constexpr bool STORE_E = false;
 };
 template <>
+struct Tiling<4, true> {
+  static constexpr int NX = 1, NY = 1;  // 4 lanes per block, 2 x 2 tiles
+  static constexpr int XM[1] = {1}, YM[1] = {2};
+  static constexpr bool STORE_E = true;
+};
+template <>
+struct Tiling<8, true> {
+  static constexpr int NX = 2, NY = 2;  // 16 lanes per block, 2 x 2 tiles
+  static constexpr int XM[2] = {3, 1}, YM[2] = {8, 4};
+  static constexpr bool STORE_E = true;
+};
+template <>
 struct Tiling<16, true> {
   static constexpr int NX = 2, NY = 2;  // 16 lanes per block, 4 x 4 tiles
   static constexpr int XM[2] = {3, 1}, YM[2] = {8, 4};

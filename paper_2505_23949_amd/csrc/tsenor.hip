@@ -197,11 +197,13 @@ inline Variant variant_of(const tsenor_problem& p) {
           (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0, p.tol > 0.0 && p.iters > 0};
 }
 
-// Below this many blocks in a launch the Dykstra kernel uses the small tiles (M = 16 and 32, double
-// iterations): with so few waves every SIMD holds at most one, whose iteration time is its instruction count.
-// Measured crossovers (M = 32: 108 us against 140 us for the 300 iterations of a few blocks; M = 16: 91 us
-// against 146 us).
-constexpr int64_t small_tiles_below_blocks(int M) { return M == 16 ? 9000 : M == 32 ? 1500 : 0; }
+// Below this many blocks in a launch the Dykstra kernel uses the small tiles (M <= 32, double iterations):
+// with so few waves every SIMD holds at most one, whose iteration time is its instruction count.
+// Measured crossovers (300 iterations of a few blocks, small against large tiles: M = 32: 108 us against 140;
+// M = 16: 91 against 146; M = 8: 46 against 84; M = 4: 35 against 90).
+constexpr int64_t small_tiles_below_blocks(int M) {
+  return M == 4 ? 50000 : M == 8 ? 9000 : M == 16 ? 9000 : M == 32 ? 1500 : 0;
+}
 
 // Below this many blocks in a launch the greedy selection runs with M lanes per block: the one-lane kernel
 // takes the time of M*M dependent steps of a single wave however few blocks there are (22 / 70 / 300 us for
@@ -306,7 +308,7 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   const auto blocks = [](const BatchEntry& e) { return e.p.nblocks; };
   int64_t total_blocks = 0;
   for (int k = 0; k < b.count; ++k) total_blocks += b.e[k].p.nblocks;
-  constexpr bool kHasSmall = M == 16 || M == 32;
+  constexpr bool kHasSmall = M <= 32;
   const bool small = kHasSmall && !v.fast && !v.zero_t && !v.adaptive &&
                      (v.tiles ? v.tiles == TSENOR_FLAG_TILES_SMALL : total_blocks < small_tiles_below_blocks(M));
   if (small) {

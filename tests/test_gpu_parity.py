@@ -309,9 +309,11 @@ def test_randomised_configurations(dev):
             assert np.array_equal(res["stats"].cpu().numpy(), ref["stats"]), desc
 
 
-@pytest.mark.parametrize("M,N,dtype", [(16, 8, "f32"), (32, 16, "bf16"), (32, 7, "f32"), (16, 3, "bf16")])
+@pytest.mark.parametrize("M,N,dtype", [(16, 8, "f32"), (32, 16, "bf16"), (32, 7, "f32"), (16, 3, "bf16"),
+                                       (4, 2, "f32"), (4, 1, "bf16"), (8, 4, "bf16"), (8, 3, "f32")])
 def test_both_tilings_of_the_dykstra_kernel(dev, M, N, dtype):
-    # ragged block counts for both tilings (M = 32: one block per wave / two; M = 16: four / eight)
+    # ragged block counts for both tilings (blocks per wave, small / large: M = 32: 1 / 2; M = 16: 4 / 8;
+    # M = 8: 4 / 16; M = 4: 16 / 64)
     import torch
 
     from paper_2505_23949_amd import binding
