@@ -547,7 +547,7 @@ def test_batched_entry_point(dev):
 
 def test_batched_mixed_variants_match_single_calls(dev):
     # 21 problems in one call: more than one fused launch holds, several block sizes and kernel variants
-    # (fp32 iterations, T = 0), degenerate N, both tau modes and dtypes, every optional output on some of them.
+    # (fp32 iterations, T = 0, early exit), degenerate N, both tau modes and dtypes, every optional output on some.
     # Every problem must come out exactly as from a call of its own, and the default variants as from the oracle.
     import torch
 
@@ -566,11 +566,14 @@ def test_batched_mixed_variants_match_single_calls(dev):
             flags = binding.TSENOR_FLAG_FP32_ITERATIONS
         if k in (5, 12):
             iters = 0
+        tol = 1e-2 if k in (2, 4, 9, 17) else 0.0      # early exit: variants of their own
+        if k == 17:
+            flags = binding.TSENOR_FLAG_FP32_ITERATIONS
         if k == 8:
             N = 0
         if k == 15:
             N = M
-        specs.append(dict(M=M, N=N, rows=rows, cols=cols, flags=flags, iters=iters, bf16=k % 3 == 1,
+        specs.append(dict(M=M, N=N, rows=rows, cols=cols, flags=flags, iters=iters, tol=tol, bf16=k % 3 == 1,
                           rel=k % 4 != 2, outputs=k % 2 == 0 and N not in (0, M)))
     keep, probs, singles, outs = [], [], [], []
     for k, s in enumerate(specs):
@@ -594,9 +597,9 @@ def test_batched_mixed_variants_match_single_calls(dev):
             kw = dict(plan_out=o["plan"], stats_out=o["stats"], tau_eff_out=o["tau_eff"], packed_out=o["packed"],
                       pruned_out=o["pruned"], objective_out=o["objective"])
         probs.append(binding.make_problem(W, s["N"], s["M"], tau, s["iters"], mask=o["mask"], col_scale=csd,
-                                          tau_mode=mode, flags=s["flags"], **kw))
+                                          tau_mode=mode, flags=s["flags"], tol=s["tol"], **kw))
         single = binding.solve(W, s["N"], s["M"], tau, s["iters"], col_scale=csd, tau_mode=mode, flags=s["flags"],
-                               want_plan=s["outputs"], want_stats=s["outputs"], want_packed=s["outputs"],
+                               tol=s["tol"], want_plan=s["outputs"], want_stats=s["outputs"], want_packed=s["outputs"],
                                want_pruned=s["outputs"], want_objective=s["outputs"])
         keep += [W, csd]
         outs.append(o)
@@ -610,7 +613,7 @@ def test_batched_mixed_variants_match_single_calls(dev):
         if s["outputs"]:
             for name in ("plan", "stats", "tau_eff", "packed", "pruned", "objective"):
                 assert torch.equal(o[name], single[name]), (k, name)
-        if s["flags"] == 0:
+        if s["flags"] == 0 and s["tol"] == 0.0:
             ref = oracle.mask(Wf, s["N"], s["M"], tau, s["iters"], col_scale=cs,
                               tau_mode=oracle.TAU_REL_MATRIX_MAX if s["rel"] else oracle.TAU_ABSOLUTE)
             assert np.array_equal(o["mask"].cpu().numpy(), ref["mask"]), k
