@@ -383,6 +383,29 @@ def test_zero_blocks_outliers_and_zero_scales(dev, M, N):
             else:
                 assert same[~tied.reshape(-1)].all(), np.flatnonzero(~same)
             assert res["tau_eff"].cpu().numpy()[0] == ref["tau_eff"]
+        # the same input with the early exit: an all-zero block has a flat kernel and stops at the first check
+        imp = oracle.importance(Wf, cs)
+        te = oracle.tau_eff(imp, tau, mode)
+        tol = 1e-4
+        log_S, done_ref = oracle.dykstra_adaptive(imp, N, M, te, iters, tol)
+        done_ref = done_ref.reshape(rows // M, cols // M)
+        assert done_ref[1, 2] == binding.TSENOR_ADAPTIVE_CHECK_EVERY
+        for flags in (0, binding.TSENOR_FLAG_FP32_ITERATIONS):
+            print(f"[case] zero blocks / outliers, early exit {N}:{M} tau={tau} mode={mode} flags={flags}", flush=True)
+            res = binding.solve(W, N, M, tau, iters, col_scale=csd, tau_mode=mode, flags=flags, tol=tol,
+                                want_plan=True, want_iters_done=True)
+            torch.cuda.synchronize()
+            done = res["iters_done"].cpu().numpy().reshape(rows // M, cols // M)
+            assert done[1, 2] == binding.TSENOR_ADAPTIVE_CHECK_EVERY and done[3, 0] == binding.TSENOR_ADAPTIVE_CHECK_EVERY
+            plan = res["plan"].cpu().numpy()
+            assert np.isfinite(plan).all()
+            assert exact.is_transposable_nm(res["mask"].cpu().numpy(), N, M)
+            agree = (done == done_ref).reshape(-1)
+            per_block = np.abs(exact.blocks(plan, M) - np.exp(exact.blocks(log_S, M))).max(axis=(1, 2))
+            if flags == 0:
+                assert np.all(np.abs(done - done_ref) <= binding.TSENOR_ADAPTIVE_CHECK_EVERY)
+                assert per_block[agree].max() <= PLAN_ATOL
+            assert per_block.max() <= FP32_PLAN_ATOL + 10 * tol
 
 
 @pytest.mark.parametrize("M,N,dtype,tol", [(32, 16, "bf16", 1e-3), (16, 8, "f32", 1e-2), (64, 32, "f32", 1e-4),
