@@ -42,6 +42,7 @@ namespace tsenor_dev {
 constexpr double kMinLogKernel = -700.0;  // exp(-700) is still a normal double
 constexpr int kIdxBits = 12;              // flat index within a block: up to 64*64 entries
 constexpr int kWarmIters = 8;             // FAST: iterations done in double before switching to fp32
+constexpr int kRowChunks64 = 2;           // M = 64: the 8 x 8 tile is loaded in this many pieces (loads in flight cost registers)
 constexpr int kChunk = 8;                 // FAST: iterations between range checks of the fp32 scalings
 constexpr int kDriftBits = 40;            // FAST: fold the fp32 scalings back beyond 2^+-kDriftBits
 constexpr double kLogFloor32 = -83.0;     // FAST: rebuilt entries are kept within [e^-83, e^55] ~ [2^-120, 2^80]
@@ -422,6 +423,8 @@ __device__ __forceinline__ void sort_half_cleaners(double (&c)[E], int q) {
         const double o = lane_xor<lm>(c[r]);
         c[r] = ((c[r] < o) == keep_min) ? c[r] : o;
       }
+      // with 64 keys per lane the scheduler otherwise starts the next stage's exchanges early and spills them
+      if constexpr (E >= 64) __builtin_amdgcn_sched_barrier(0);
     }
     sort_half_cleaners<E, LPB, J / 2>(c, q);
   }
@@ -446,9 +449,19 @@ __device__ __forceinline__ void sort_ascending(double (&c)[E], int q) {
         c[r] = ((c[r] < o_lo) == keep_min) ? c[r] : o_lo;
         c[E - 1 - r] = ((c[E - 1 - r] < o_hi) == keep_min) ? c[E - 1 - r] : o_hi;
       }
+      if constexpr (E >= 64) __builtin_amdgcn_sched_barrier(0);
     }
     sort_half_cleaners<E, LPB, K / 4>(c, q);
     sort_ascending<E, LPB, K * 2>(c, q);
+  }
+}
+
+// calls f(integral_constant<A0>) for A0 = 0, NA, 2 NA, ... < TH: a tile is loaded NA rows at a time
+template <int A0, int NA, int TH, class F>
+__device__ __forceinline__ void row_chunks(F& f) {
+  if constexpr (A0 < TH) {
+    f(std::integral_constant<int, A0>{});
+    row_chunks<A0 + NA, NA, TH>(f);
   }
 }
 
@@ -512,10 +525,13 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
     for (int b = 0; b < TW; ++b) cj[b] = gx * TW + (b ^ ryp);
     return tile_addr<TH, TW>(p, r0, c0, ri, cj);
   };
-  // the fp32 variant lives in half the registers: it loads a tile in two halves
-  constexpr int NA = (FAST && TH >= 8) ? TH / 2 : TH;
+  // rows of a tile loaded at a time: the fp32 variant lives in half the registers (two halves); the 8 x 8
+  // tiles of M = 64 would keep 64 loads with their addresses in flight and spill
+  constexpr int NA = M == 64 ? TH / kRowChunks64 : (FAST && TH >= 8) ? TH / 2 : TH;
 
-  double kap[TH][TW];
+  double c[E];  // sort keys
+  int iters_done = 0;
+  double kap[ZERO_T ? 1 : TH][ZERO_T ? 1 : TW];
   // Normaliser of every in-kernel row: kappa = exp(K - mrow) <= ~1.  Any per-row constant gives the same
   // iterates, because the first step of Algorithm 1 rescales every row (with TSENOR_FLAG_COLS_FIRST: every
   // column, which is the in-kernel row); a single precision value a little above the row's largest K is
@@ -523,7 +539,28 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
   // block below the range of a double.
   float mrow[TH];
   {
-    const auto addr = addr_of(fresh(rx), fresh(ry));
+    const int rx0 = fresh(rx), ry0 = fresh(ry);
+    const auto addr = addr_of(rx0, ry0);
+    // the plan (a diagnostic output) in a pass of its own, before the keys exist and with its own loads: an
+    // exp() inside the key pass, or keys kept alive across it, costs registers (spills for M = 64)
+    if constexpr (ZERO_T) {
+      if (plan_out && active) {
+        auto plan_rows = [&](auto first) {
+          constexpr int A0 = decltype(first)::value;
+          float imp[NA][TW];
+          tile_importance<A0, NA>(p, addr, imp);
+#pragma unroll
+          for (int a = 0; a < NA; ++a)
+#pragma unroll
+            for (int b = 0; b < TW; ++b) {
+              const int ri = gy * TH + ((A0 + a) ^ rx0), cj = gx * TW + (b ^ ry0);
+              plan_out[(r0 + mat_row(ri, cj)) * p.cols + c0 + mat_col(ri, cj)] = exp(tau_eff * (double)imp[a][b]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        row_chunks<0, NA, TH>(plan_rows);
+      }
+    }
     auto rows = [&](auto first) {
       constexpr int A0 = decltype(first)::value;
       float imp[NA][TW];
@@ -532,36 +569,27 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
       for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int b = 0; b < TW; ++b) {
-          kap[A0 + a][b] = tau_eff * (double)imp[a][b];  // K of Algorithm 1 line 1
-          const float up = __double2float_ru(kap[A0 + a][b]);
-          mrow[A0 + a] = b == 0 ? up : fmaxf(mrow[A0 + a], up);
+          const double K = tau_eff * (double)imp[a][b];  // K of Algorithm 1 line 1
+          if constexpr (ZERO_T) {
+            // no iterations: the greedy order is descending K itself.  Bit patterns of non-negative doubles
+            // order like the doubles: pattern(2^1023) - pattern(K) reverses the order for every finite
+            // K >= 0 and is again the pattern of a positive double
+            const int ri = gy * TH + ((A0 + a) ^ rx0), cj = gx * TW + (b ^ ry0);
+            const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
+            const unsigned long long bits = (unsigned long long)__double_as_longlong(K);
+            const unsigned long long key = (0x7FE0000000000000ull - bits) & ~((1ull << kIdxBits) - 1);
+            c[(A0 + a) * TW + b] = __longlong_as_double((long long)(key | idx));
+          } else {
+            kap[A0 + a][b] = K;
+            const float up = __double2float_ru(K);
+            mrow[A0 + a] = b == 0 ? up : fmaxf(mrow[A0 + a], up);
+          }
         }
     };
-    rows(std::integral_constant<int, 0>{});
-    if constexpr (NA < TH) rows(std::integral_constant<int, NA>{});
+    row_chunks<0, NA, TH>(rows);
   }
-  all_reduce_max_x<T, TH>(mrow);
-
-  double c[E];  // sort keys
-  int iters_done = 0;
-  if constexpr (ZERO_T) {
-    // no iterations: the greedy order is descending K itself
-    const int rx0 = fresh(rx), ry0 = fresh(ry);
-#pragma unroll
-    for (int a = 0; a < TH; ++a)
-#pragma unroll
-      for (int b = 0; b < TW; ++b) {
-        const int ri = gy * TH + (a ^ rx0), cj = gx * TW + (b ^ ry0);
-        const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
-        const unsigned long long bits = (unsigned long long)__double_as_longlong(kap[a][b]);
-        // bit patterns of non-negative doubles order like the doubles: pattern(2^1023) - pattern(K) reverses
-        // the order for every finite K >= 0 and is again the pattern of a positive double
-        const unsigned long long key = (0x7FE0000000000000ull - bits) & ~((1ull << kIdxBits) - 1);
-        c[a * TW + b] = __longlong_as_double((long long)(key | idx));
-        if (plan_out && active)
-          plan_out[(r0 + mat_row(ri, cj)) * p.cols + c0 + mat_col(ri, cj)] = exp(kap[a][b]);
-      }
-  } else {
+  if constexpr (!ZERO_T) {
+    all_reduce_max_x<T, TH>(mrow);
 #pragma unroll
     for (int a = 0; a < TH; ++a)
 #pragma unroll
@@ -665,8 +693,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
                 __builtin_amdgcn_sched_barrier(0);
               }
           };
-          rows(std::integral_constant<int, 0>{});
-          if constexpr (NA < TH) rows(std::integral_constant<int, NA>{});
+          row_chunks<0, NA, TH>(rows);
 #pragma unroll
           for (int a = 0; a < TH; ++a) U32[a] = Uinv32[a] = 1.0f;
 #pragma unroll
@@ -727,6 +754,31 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
     all_gather_x<T, double, TH>(lu);
     all_gather_y<T, double, TW>(lv);
     const auto addr = addr_of(rx2, ry2);
+    // log S^(T) = min(K + f_i + g_j, 0)
+    // (K is not floored here as it is for kappa: entries too small for the iterations to see keep
+    // their own order in the scan)
+    auto log_plan = [&](float importance, int a, int b) {
+      const double K = tau_eff * (double)importance;
+      return fmin((K - (double)mrow[a]) + (lu[a] + lv[b]), 0.0);
+    };
+    // the plan (a diagnostic output) in a pass of its own, with its own loads: an exp() inside the key pass
+    // costs it registers (spills for M = 64)
+    if (plan_out && active) {
+      auto plan_rows = [&](auto first) {
+        constexpr int A0 = decltype(first)::value;
+        float imp[NA][TW];
+        tile_importance<A0, NA>(p, addr, imp);
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+          for (int b = 0; b < TW; ++b) {
+            const int ri = gy * TH + ((A0 + a) ^ rx2), cj = gx * TW + (b ^ ry2);
+            plan_out[(r0 + mat_row(ri, cj)) * p.cols + c0 + mat_col(ri, cj)] = exp(log_plan(imp[a][b], A0 + a, b));
+            __builtin_amdgcn_sched_barrier(0);
+          }
+      };
+      row_chunks<0, NA, TH>(plan_rows);
+    }
     auto rows = [&](auto first) {
       constexpr int A0 = decltype(first)::value;
       float imp[NA][TW];
@@ -736,12 +788,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
 #pragma unroll
         for (int b = 0; b < TW; ++b) {
           const int ri = gy * TH + ((A0 + a) ^ rx2), cj = gx * TW + (b ^ ry2);
-          const double K = tau_eff * (double)imp[a][b];
-          // log S^(T) = min(K + f_i + g_j, 0)
-          // (K is not floored here as it is for kappa: entries too small for the iterations to see keep
-          // their own order in the scan)
-          const double key = fmin((K - (double)mrow[A0 + a]) + (lu[A0 + a] + lv[b]), 0.0);
-          if (plan_out && active) plan_out[(r0 + mat_row(ri, cj)) * p.cols + c0 + mat_col(ri, cj)] = exp(key);
+          const double key = log_plan(imp[a][b], A0 + a, b);
           const unsigned long long idx = (unsigned long long)(mat_row(ri, cj) * M + mat_col(ri, cj));
           const unsigned long long bits = (unsigned long long)__double_as_longlong(fabs(key));
           // descending key, ties by ascending flat index; + 2^52 keeps the pattern a normal double
@@ -749,11 +796,15 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
               __longlong_as_double((long long)(((bits & ~((1ull << kIdxBits) - 1)) | idx) + (1ull << 52)));
         }
     };
-    rows(std::integral_constant<int, 0>{});
-    if constexpr (NA < TH) rows(std::integral_constant<int, NA>{});
+    row_chunks<0, NA, TH>(rows);
   }
 
   sort_ascending<E, LPB>(c, q);
+  // The stores below sit under `active`, and only the index bits of a key are stored: the compiler would move
+  // the last stage's selects into that branch but has to leave its cross-lane moves outside, all of them
+  // alive at once (spills for M = 64).  Using the keys here keeps every select next to its moves.
+#pragma unroll
+  for (int r = 0; r < E; ++r) asm volatile("" : "+v"(c[r]));
 
   if (active && q == 0 && batch.e[which].iters_done_out) batch.e[which].iters_done_out[blk] = iters_done;
   if (active) {
