@@ -21,7 +21,7 @@
 // kept as logarithms.  fp32 has 8 exponent bits, so every kChunk iterations the relative scalings are
 // checked and, when one has drifted past 2^+-kDriftBits, their logarithms are added to the double ones and
 // kappa32 is rebuilt as fl32(exp(K - row max + log U + log V)) from a fresh read of the importance (kappa
-// itself is not kept: the kernel is budgeted 168 registers).  Rebuilt entries are clamped to about
+// itself is not kept: the kernel is budgeted the registers of three waves per SIMD).  Rebuilt entries are clamped to about
 // [2^-120, 2^80]; within the drift bound (2^+-80 for a product of a row and a column scaling) a clamped
 // entry is still >= 1 (capped) or <= 2^-40 (nothing).
 //
@@ -472,9 +472,9 @@ struct DykstraLaunch {
   static constexpr int kWavesPerGroup = ADAPT ? 1 : 4;
   static constexpr int kThreads = kWavesPerGroup * kWave;
   // waves per SIMD the register budget is set for.  The fp32 loop wants more than two (one wave issues at
-  // most every ~5 cycles, an fp32 instruction occupies the SIMD for 2); its state fits 128 registers, but at
-  // three waves (168 registers) the double-precision phases and the sort spill less, and that measured 4 %
-  // faster than four waves.  The double-precision loop holds twice the state: two waves of up to 256 registers.
+  // most every ~5 cycles, an fp32 instruction occupies the SIMD for 2); the kernel needs 158 registers, which
+  // fits three waves (168 each) without spills; four waves (128, a few spills outside the loop) measured the
+  // same.  The double-precision loop holds twice the state: two waves of up to 256 registers.
   static constexpr int kWavesPerSimd = (FAST && M <= 32) ? 3 : 2;
 };
 
