@@ -312,76 +312,63 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
   return worst;
 }
 
-// min of two floats as the bare instruction.  fminf() makes the compiler quiet possible signalling NaNs in
-// operands it has not computed itself (one extra v_max per value read back from LDS); nothing here is a NaN
-// unless the input was, and then any result will do.
-__device__ __forceinline__ float raw_min(float a, float b) {
+// x * y with the result clamped to [0, 1] by the output modifier: one instruction at the full fp32 rate
+// (measured on MI355X: 1.2 ns per wave-instruction per SIMD, as a plain v_mul_f32; v_min_f32 / v_max_f32 /
+// v_med3_f32 take 1.9 ns).  Written as the bare instruction so that it stays this one.
+__device__ __forceinline__ float mul_clamp01(float x, float y) {
   float r;
-  asm("v_min_f32_e32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  asm("v_mul_f32_e64 %0, %1, %2 clamp" : "=v"(r) : "v"(x), "v"(y));
   return r;
 }
 
-// The same iteration in single precision, arranged so that every per-entry operation is a plain two- or
-// three-operand fp32 instruction (the clamp output modifier needs the long encoding, which issues at half
-// the fp32 rate).  With e'_ij = min(kappa_ij V_j, 1/U_i) = e_ij / U_i:
-//     sum_j e'_ij = (sum_j e_ij) / U_i,  so  U_i R_i = N / sum_j e'_ij   and   sum_i e_ij R_i = sum_i e'_ij (U_i R_i).
-// U, Uinv: scaling of every tile row and its reciprocal; V: scaling of every tile column.  A row scaling
-// grows by at most 2^10 per iteration (keeps everything finite on degenerate input).
-// ADAPT as in dykstra_iteration: the row factor of this form is Un_i / U_i.
+// The same iteration in single precision.  kap stays as rebuilt (no rounding accumulates in it); the scalings
+// U (every tile row) and V (every tile column) are kept as numbers, and the capped entry is
+//     e_ij = clamp(kap_ij * (U_i V_j)):  a multiply, a multiply with the clamp modifier, the add of the row
+// sum and the multiply-add of the column sum per entry, all at the full fp32 rate.  A scaling grows by at most
+// 2^10 per iteration (keeps everything finite on degenerate input).
+// ADAPT as in dykstra_iteration.
 template <class T, bool LDS_GATHER = false, bool ADAPT = false, int TH, int TW>
-__device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW], float (&U)[TH], float (&Uinv)[TH],
-                                                       float (&V)[TW], float Nf, float2* xr = nullptr, int rx = 0,
+__device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW], float (&U)[TH], float (&V)[TW],
+                                                       float Nf, float* xr = nullptr, int rx = 0,
                                                        bool frozen = false) {
   constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
   float worst = 0;
-  float e[TH][TW], S[TH], C[TW];
+  float e[TH][TW], R[TH], C[TW];
 #pragma unroll
   for (int a = 0; a < TH; ++a) {
 #pragma unroll
     for (int b = 0; b < TW; ++b) {
-      e[a][b] = raw_min(kap[a][b] * V[b], Uinv[a]);
-      S[a] = b == 0 ? e[a][b] : S[a] + e[a][b];
+      e[a][b] = mul_clamp01(kap[a][b], U[a] * V[b]);
+      R[a] = b == 0 ? e[a][b] : R[a] + e[a][b];
     }
   }
-  reduce_scatter_x<T, float, TH>(S);
-  float Un[TH];
+  reduce_scatter_x<T, float, TH>(R);
 #pragma unroll
   for (int a = 0; a < OWN_R; ++a) {
-    Un[a] = fminf(Nf * fast_rcp(S[a]), U[a] * 1024.0f);  // new scaling of an owned row
+    R[a] = fminf(Nf * fast_rcp(R[a]), 1024.0f);  // factor of an owned row (a NaN from an empty row gives the cap)
     if constexpr (ADAPT) {
-      worst = fmaxf(worst, fabsf(fmaf(Un[a], Uinv[a], -1.0f)));
-      Un[a] = frozen ? U[a] : Un[a];
-      S[a] = frozen ? Uinv[a] : fast_rcp(Un[a]);
-    } else {
-      S[a] = fast_rcp(Un[a]);  // and its reciprocal
+      worst = fmaxf(worst, fabsf(R[a] - 1.0f));
+      R[a] = frozen ? 1.0f : R[a];
     }
   }
   if constexpr (LDS_GATHER) {
-    // scaling and reciprocal of the owned row through LDS as one pair (see dykstra_iteration)
+    // the factor of the owned row through LDS (see dykstra_iteration)
     static_assert(OWN_R == 1, "one owned row per lane");
-    xr[rx] = make_float2(Un[0], S[0]);
+    xr[rx] = R[0];
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int a = 0; a < TH; ++a) {
-      const float2 got = xr[a ^ rx];
-      U[a] = got.x;
-      Uinv[a] = got.y;
-    }
+    for (int a = 0; a < TH; ++a) R[a] = xr[a ^ rx];
     asm volatile("" ::: "memory");
   } else {
-    all_gather_x<T, float, TH>(Un);
-    all_gather_x<T, float, TH>(S);
-#pragma unroll
-    for (int a = 0; a < TH; ++a) {
-      U[a] = Un[a];
-      Uinv[a] = S[a];
-    }
+    all_gather_x<T, float, TH>(R);
   }
 #pragma unroll
   for (int b = 0; b < TW; ++b) {
 #pragma unroll
-    for (int a = 0; a < TH; ++a) C[b] = a == 0 ? e[a][b] * U[a] : fmaf(e[a][b], U[a], C[b]);
+    for (int a = 0; a < TH; ++a) C[b] = a == 0 ? e[a][b] * R[a] : fmaf(e[a][b], R[a], C[b]);
   }
+#pragma unroll
+  for (int a = 0; a < TH; ++a) U[a] *= R[a];
   reduce_scatter_y<T, float, TW>(C);
 #pragma unroll
   for (int b = 0; b < OWN_C; ++b) {
@@ -666,7 +653,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
       if (p.T > kWarmIters && !(ADAPT && __all(frozen))) {
         // fp32 phase: kap32 = fl32(kap U V) for the double scalings U V reached so far, and fp32 scalings
         // U32, V32 relative to them.  kap is not kept: a rebuild reloads the importance.
-        float kap32[TH][TW], U32[TH], Uinv32[TH], V32[TW];
+        float kap32[TH][TW], U32[TH], V32[TW];
         const float Nf = (float)p.N;
         const float hi = __builtin_ldexpf(1.0f, kDriftBits), lo = __builtin_ldexpf(1.0f, -kDriftBits);
         auto rebuild = [&]() {
@@ -695,7 +682,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
           };
           row_chunks<0, NA, TH>(rows);
 #pragma unroll
-          for (int a = 0; a < TH; ++a) U32[a] = Uinv32[a] = 1.0f;
+          for (int a = 0; a < TH; ++a) U32[a] = 1.0f;
 #pragma unroll
           for (int b = 0; b < TW; ++b) V32[b] = 1.0f;
         };
@@ -716,19 +703,19 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
         for (int t = kWarmIters; t < p.T && !all_frozen;) {
           const int stop = (p.T - t > kChunk) ? t + kChunk : p.T;
           constexpr bool kLdsGather32 = M == 32 || M == 64;
-          __shared__ float2 xrows32[kLdsGather32 ? WPG : 1][kLdsGather32 ? kWave / 8 : 1][8];
-          float2* xr = kLdsGather32 ? &xrows32[wave_in_group][lane / 8][0] : nullptr;
+          __shared__ float xrows32[kLdsGather32 ? WPG : 1][kLdsGather32 ? kWave / 8 : 1][8];
+          float* xr = kLdsGather32 ? &xrows32[wave_in_group][lane / 8][0] : nullptr;
           if constexpr (ADAPT) {
             for (; t < stop && !all_frozen; ++t) {
               const float worst =
-                  dykstra_iteration_f32<T, kLdsGather32, true>(kap32, U32, Uinv32, V32, Nf, xr, rx, frozen);
+                  dykstra_iteration_f32<T, kLdsGather32, true>(kap32, U32, V32, Nf, xr, rx, frozen);
               if ((t + 1) % TSENOR_ADAPTIVE_CHECK_EVERY == 0) {
                 freeze_if(block_max<LPB>((double)worst) <= p.tol, t + 1);
                 all_frozen = __all(frozen);
               }
             }
           } else {
-            for (; t < stop; ++t) dykstra_iteration_f32<T, kLdsGather32>(kap32, U32, Uinv32, V32, Nf, xr, rx);
+            for (; t < stop; ++t) dykstra_iteration_f32<T, kLdsGather32>(kap32, U32, V32, Nf, xr, rx);
           }
           float mxs = U32[0], mns = U32[0];
 #pragma unroll
