@@ -22,14 +22,21 @@ FLAGS = [
 ]
 
 
+# measurement aid, a program of its own: issue rate of single vector instructions (see its header)
+PROBE_SOURCE = PKG / "csrc" / "issue_rate_probe.hip"
+PROBE_OUTPUT = PKG / "issue_rate_probe.bin"
+PROBE_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
 def build(verbose: bool = False) -> Path:
-    """Compile every HIP source into libtsenor.so (always recompiles)."""
-    tmp = OUTPUT.with_suffix(f".so.tmp{os.getpid()}")
-    cmd = [HIPCC, *FLAGS, "-o", str(tmp), *map(str, SOURCES)]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    os.replace(tmp, OUTPUT)
+    """Compile every HIP source: libtsenor.so and the issue-rate probe (always recompiles)."""
+    for flags, sources, output in ((FLAGS, SOURCES, OUTPUT), (PROBE_FLAGS, [PROBE_SOURCE], PROBE_OUTPUT)):
+        tmp = output.with_suffix(output.suffix + f".tmp{os.getpid()}")
+        cmd = [HIPCC, *flags, "-o", str(tmp), *map(str, sources)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, output)
     return OUTPUT
 
 
