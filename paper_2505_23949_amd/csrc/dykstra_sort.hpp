@@ -312,27 +312,6 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
   return worst;
 }
 
-// exp(x) to single-precision accuracy (~1e-7 relative) for the fp32-iteration mode, whose entries are rounded
-// to fp32 anyway: x log2(e) = n + f with n an integer and |f| <= 1/2 (both exact in double), 2^f from the
-// hardware's single-precision exp2, scaled by 2^n.  Seven instructions instead of the ~40 of a double exp().
-// Range: |x| < 700 for the double result, [-87, 88] for the float result.
-__device__ __forceinline__ float exp_parts(double x, int& n) {
-  const double t = x * 1.4426950408889634074;
-  const double r = __builtin_rint(t);
-  n = (int)r;
-  return __builtin_amdgcn_exp2f((float)(t - r));
-}
-__device__ __forceinline__ float exp_as_float(double x) {
-  int n;
-  const float m = exp_parts(x, n);
-  return __builtin_ldexpf(m, n);
-}
-__device__ __forceinline__ double exp_single_accuracy(double x) {
-  int n;
-  const float m = exp_parts(x, n);
-  return __builtin_ldexp((double)m, n);
-}
-
 // x * y with the result clamped to [0, 1] by the output modifier: one instruction at the full fp32 rate
 // (measured on MI355X: 1.2 ns per wave-instruction per SIMD, as a plain v_mul_f32; v_min_f32 / v_max_f32 /
 // v_med3_f32 take 1.9 ns).  Written as the bare instruction so that it stays this one.
@@ -602,9 +581,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
     for (int a = 0; a < TH; ++a)
 #pragma unroll
       for (int b = 0; b < TW; ++b) {
-        const double x = fmax(kap[a][b] - (double)mrow[a], kMinLogKernel);
-        // (the fp32-iteration mode carries single-precision noise anyway)
-        kap[a][b] = FAST ? exp_single_accuracy(x) : exp(x);
+        kap[a][b] = exp(fmax(kap[a][b] - (double)mrow[a], kMinLogKernel));
         __builtin_amdgcn_sched_barrier(0);  // one exp at a time: interleaving them only costs registers
       }
 
@@ -699,7 +676,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
               for (int b = 0; b < TW; ++b) {
                 const double K = tau_eff * (double)imp[a][b];
                 const double full = (K - (double)mrow[A0 + a]) + (lu[A0 + a] + lv[b]);
-                kap32[A0 + a][b] = exp_as_float(fmin(fmax(full, kLogFloor32), kLogCeil32));
+                kap32[A0 + a][b] = (float)exp(fmin(fmax(full, kLogFloor32), kLogCeil32));
                 __builtin_amdgcn_sched_barrier(0);
               }
           };
