@@ -39,10 +39,19 @@ __global__ void init_kernel(Batch batch) {
   for (int k = 0; k < 4; ++k) hdr->stats[k] = 0ull;
 }
 
+constexpr int kAbsmaxInFlight = 4;  // rows read per thread before any is used
+// threads of a workgroup that share a row: the smallest power of two that covers its vectors
+__host__ __device__ inline int absmax_threads_per_row(int64_t vectors_per_row, int threads) {
+  int tpr = 1;
+  while (tpr < vectors_per_row && tpr < threads) tpr <<= 1;
+  return tpr;
+}
+
 // Largest importance of every matrix of the batch that uses the relative tau (App. B.1 parameter choice).
 // blockIdx.z: matrix; x and y stride over its columns and rows.  With absmax_vec every thread reads 8
 // consecutive weights of a row with 16-byte loads (needs cols % 8 == 0 and 16-byte aligned rows and column
-// scale); otherwise one weight at a time.
+// scale); otherwise one weight at a time.  A matrix with fewer than 256 such vectors per row shares the
+// workgroup between rows.
 __global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
   const BatchEntry& e = batch.e[blockIdx.z];
   const DevProblem p = e.p;
@@ -51,8 +60,10 @@ __global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
   float m = 0.0f;
   if (e.absmax_vec) {
     const int64_t vpr = p.cols / 8;  // 8-weight vectors per row
-    constexpr int kInFlight = 4;     // rows read per thread before any is used
-    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < vpr; v += (int64_t)gridDim.x * blockDim.x) {
+    // a narrow matrix shares the workgroup between rows: tpr threads per row, blockDim.x / tpr rows per pass
+    const int tpr = absmax_threads_per_row(vpr, (int)blockDim.x), rpp = (int)blockDim.x / tpr;
+    const int tv = (int)threadIdx.x % tpr, tr = (int)threadIdx.x / tpr;
+    for (int64_t v = (int64_t)blockIdx.x * tpr + tv; v < vpr; v += (int64_t)gridDim.x * tpr) {
       float c[8] = {1.0f, 1.0f, 1.0f, 1.0f, 1.0f, 1.0f, 1.0f, 1.0f};  // times exactly 1 where there is no scale
       if (p.col_scale) {
         const float4* cs = reinterpret_cast<const float4*>(p.col_scale + v * 8);
@@ -62,16 +73,16 @@ __global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
       // a workgroup streams a contiguous band of rows (rows far apart cost a page-table walk per load)
       const int64_t band = (rows + gridDim.y - 1) / gridDim.y;
       const int64_t r_end = (blockIdx.y + 1) * band < rows ? (blockIdx.y + 1) * band : rows;
-      for (int64_t r = blockIdx.y * band; r < r_end; r += kInFlight) {
+      for (int64_t r = blockIdx.y * band + (int64_t)tr * kAbsmaxInFlight; r < r_end; r += (int64_t)rpp * kAbsmaxInFlight) {
         if (p.dtype == TSENOR_BF16) {
-          uint4 raw[kInFlight];
+          uint4 raw[kAbsmaxInFlight];
 #pragma unroll
-          for (int u = 0; u < kInFlight; ++u) {
+          for (int u = 0; u < kAbsmaxInFlight; ++u) {
             const int64_t ru = r + u < r_end ? r + u : r;
             raw[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned short*>(p.W) + ru * p.ld + v * 8);
           }
 #pragma unroll
-          for (int u = 0; u < kInFlight; ++u) {
+          for (int u = 0; u < kAbsmaxInFlight; ++u) {
             const unsigned int w[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -80,16 +91,16 @@ __global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
             }
           }
         } else {
-          float4 lo[kInFlight], hi[kInFlight];
+          float4 lo[kAbsmaxInFlight], hi[kAbsmaxInFlight];
 #pragma unroll
-          for (int u = 0; u < kInFlight; ++u) {
+          for (int u = 0; u < kAbsmaxInFlight; ++u) {
             const int64_t ru = r + u < r_end ? r + u : r;
             const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.W) + ru * p.ld + v * 8);
             lo[u] = src[0];
             hi[u] = src[1];
           }
 #pragma unroll
-          for (int u = 0; u < kInFlight; ++u) {
+          for (int u = 0; u < kAbsmaxInFlight; ++u) {
             const float w[8] = {lo[u].x, lo[u].y, lo[u].z, lo[u].w, hi[u].x, hi[u].y, hi[u].z, hi[u].w};
 #pragma unroll
             for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(w[k]) * c[k]);
@@ -261,14 +272,21 @@ BatchEntry entry_of(const tsenor_problem& p, char* ws) {
 
 // grid of the kernels that stride over a matrix 8 weights (or 1) at a time: x over a row, y over rows,
 // about `target` workgroups in all, sized for the largest matrix of the batch
-dim3 strided_grid(const Batch& b, bool vec_only, unsigned target) {
+dim3 strided_grid(const Batch& b, bool vec_only, unsigned target, bool for_absmax) {
   unsigned gx = 1, gy = 1;
   for (int k = 0; k < b.count; ++k) {
     const BatchEntry& e = b.e[k];
     const int64_t per_row = (vec_only || e.absmax_vec) ? e.p.cols / 8 : e.p.cols;
     const unsigned x = (unsigned)std::min<int64_t>((per_row + 255) / 256, 16);
     gx = std::max(gx, x);
-    gy = std::max(gy, (unsigned)std::min<int64_t>(e.rows, std::max<unsigned>(target / x, 1)));
+    int64_t bands = std::min<int64_t>(e.rows, std::max<unsigned>(target / x, 1));
+    if (for_absmax && e.absmax_vec) {
+      // enough rows per workgroup to give every thread its rows in flight (a narrow matrix shares the
+      // workgroup between rows), and no more workgroups than that: each ends in an atomic on one address
+      const int64_t rows_per_group = (int64_t)(256 / absmax_threads_per_row(per_row, 256)) * kAbsmaxInFlight;
+      bands = std::min(bands, (e.rows + rows_per_group - 1) / rows_per_group);
+    }
+    gy = std::max(gy, (unsigned)bands);
   }
   return dim3(gx, gy, (unsigned)b.count);
 }
@@ -302,7 +320,7 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   }
   mark(0);
   init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
-  if (any_rel) absmax_kernel<<<strided_grid(b, false, 512), 256, 0, stream>>>(b);
+  if (any_rel) absmax_kernel<<<strided_grid(b, false, 512, true), 256, 0, stream>>>(b);
   mark(1);
   constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
   const auto blocks = [](const BatchEntry& e) { return e.p.nblocks; };
@@ -354,7 +372,7 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   if (!assign_groups(b, blocks, kWave / M)) return TSENOR_ERR_SHAPE;
   finalize_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
   if (any_objective) objective_kernel<<<b.count, 1024, 0, stream>>>(b);
-  if (any_emit) emit_kernel<<<strided_grid(b, true, 2048), 256, 0, stream>>>(b);
+  if (any_emit) emit_kernel<<<strided_grid(b, true, 2048, false), 256, 0, stream>>>(b);
   if (any_stats) stats_kernel<<<1, 4 * kMaxBatch, 0, stream>>>(b);
   mark(4);
   return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
@@ -383,7 +401,7 @@ int run_degenerate(const tsenor_problem& p, char* ws, hipStream_t stream, hipEve
   b.e[0] = entry_of(p, ws);
   init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
   if (p.stats_out) stats_kernel<<<1, 4 * kMaxBatch, 0, stream>>>(b);
-  if (p.packed_out || p.pruned_out) emit_kernel<<<strided_grid(b, true, 2048), 256, 0, stream>>>(b);
+  if (p.packed_out || p.pruned_out) emit_kernel<<<strided_grid(b, true, 2048, false), 256, 0, stream>>>(b);
   if (ev) (void)hipEventRecord(ev[4], stream);
   return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
 }
