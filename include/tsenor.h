@@ -93,7 +93,7 @@ enum {
   /* How the Dykstra kernel spreads a block over lanes.  Same arithmetic, same results up to the order of
    * the additions inside a row or column sum (~1e-15).  LARGE tiles: 32 entries per lane (16 for M <= 8),
    * fewest instructions per entry: best for full matrices.  SMALL tiles (M <= 32, double-precision
-   * iterations with iters > 0 and no early exit; ignored otherwise): 16 entries per lane (4 for M <= 8),
+   * iterations with iters > 0; ignored otherwise): 16 entries per lane (4 for M <= 8),
    * more lanes per block, a shorter dependent chain per iteration: best while the launch cannot fill the
    * chip anyway.  Default: chosen by the number of blocks in the launch.  Setting both is an error. */
   TSENOR_FLAG_TILES_LARGE = 1u << 5,

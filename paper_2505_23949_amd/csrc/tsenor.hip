@@ -327,14 +327,20 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   int64_t total_blocks = 0;
   for (int k = 0; k < b.count; ++k) total_blocks += b.e[k].p.nblocks;
   constexpr bool kHasSmall = M <= 32;
-  const bool small = kHasSmall && !v.fast && !v.zero_t && !v.adaptive &&
+  const bool small = kHasSmall && !v.fast && !v.zero_t &&
                      (v.tiles ? v.tiles == TSENOR_FLAG_TILES_SMALL : total_blocks < small_tiles_below_blocks(M));
   if (small) {
     if constexpr (kHasSmall) {
-      using L = DykstraLaunch<M, false>;
       constexpr int BPWS = kWave >> (Tiling<M, true>::NX + Tiling<M, true>::NY);
-      if (!assign_groups(b, blocks, (int64_t)BPWS * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
-      dykstra_sort_kernel<M, false, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
+      if (v.adaptive) {
+        using L = DykstraLaunch<M, false, true>;
+        if (!assign_groups(b, blocks, (int64_t)BPWS * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
+        dykstra_sort_kernel<M, false, false, true, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
+      } else {
+        using L = DykstraLaunch<M, false>;
+        if (!assign_groups(b, blocks, (int64_t)BPWS * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
+        dykstra_sort_kernel<M, false, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
+      }
     }
   } else if (v.fast && v.adaptive) {
     using L = DykstraLaunch<M, true, true>;

@@ -421,10 +421,12 @@ def test_early_exit_of_the_iterations(dev, M, N, dtype, tol):
     w = synth.Workload(f"early_exit_{N}of{M}", 6 * M, 9 * M, N, M, 0.01, 600, dtype, "wanda", 7300 + M)
     g = synth.generate(w)
     W, cs = _to_device(g, w, dev)
-    for cols_first in (False, True):
-        print(f"[case] early exit {w.name} tol={tol} cols_first={cols_first}", flush=True)
+    for cols_first, tiles in ((False, binding.TSENOR_FLAG_TILES_LARGE), (True, binding.TSENOR_FLAG_TILES_LARGE),
+                              (False, binding.TSENOR_FLAG_TILES_SMALL), (True, binding.TSENOR_FLAG_TILES_SMALL)):
+        print(f"[case] early exit {w.name} tol={tol} cols_first={cols_first} tiles={tiles}", flush=True)
         res = binding.solve(W, N, M, w.tau, w.iters, col_scale=cs, tau_mode=w.tau_mode, tol=tol, want_plan=True,
-                            want_iters_done=True, flags=binding.TSENOR_FLAG_COLS_FIRST if cols_first else 0)
+                            want_iters_done=True,
+                            flags=tiles | (binding.TSENOR_FLAG_COLS_FIRST if cols_first else 0))
         torch.cuda.synchronize()
         imp = oracle.importance(g["W_f32"], g["col_scale"])
         te = oracle.tau_eff(imp, w.tau, w.tau_mode)
