@@ -77,8 +77,8 @@ enum {
   /* project onto the column-sum set before the row-sum set (the order of the listing in App. A.2);
    * default is rows first as in Algorithm 1 */
   TSENOR_FLAG_COLS_FIRST = 1u << 1,
-  /* Run the Dykstra iterations after the eighth in single precision (twice the vector issue rate of
-   * double on MI355X).  The potentials then carry ~1e-6 of rounding noise: the plan agrees with a
+  /* Run the Dykstra iterations after the eighth in single precision (single-precision multiplies and
+   * adds issue 1.5-1.8 times as fast as double-precision ones on MI355X).  The potentials then carry ~1e-6 of rounding noise: the plan agrees with a
    * double-precision evaluation to ~1e-5 instead of ~1e-13, and the greedy order - hence the mask - can
    * differ from it in a block where two plan entries are closer than that (none in 8192 blocks of the
    * 16:32 test workload).  Sort keys, swap scores and all results stay in double.  Off by default. */
