@@ -390,30 +390,55 @@ __device__ __forceinline__ void compare_exchange(double& lo, double& hi) {
   hi = b;
 }
 
+// min(a, -b) as one instruction (fmin() would first quiet possible signalling NaNs in operands the compiler
+// has not computed itself, one more instruction each)
+__device__ __forceinline__ double min_with_negated(double a, double b) {
+  double r;
+  asm("v_min_f64 %0, %1, -%2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+// Sign convention of the keys between sort stages: the lanes whose bit SB is set hold their keys negated
+// (SB = 0: nobody).  Moves from convention SB to convention B: one xor per key in the lanes that change.
+template <int SB, int B, int E>
+__device__ __forceinline__ void sort_resign(double (&c)[E], int q) {
+  if constexpr (SB != B) {
+    const bool flip = ((q & SB) != 0) != ((q & B) != 0);
+    const int mask = flip ? (int)0x80000000 : 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) c[r] = __hiloint2double(__double2hiint(c[r]) ^ mask, __double2loint(c[r]));
+  }
+}
+
 // Ascending bitonic sort of E*LPB distinct positive doubles spread over LPB lanes (position q*E + r).
 // Every merge starts with the mirrored compare (position p against p ^ (k-1)), after which the smaller
 // key always belongs at the lower position, so no direction flags are needed.
-template <int E, int LPB, int J>
+// A stage across lanes: the lane whose bit is clear keeps the smaller of its key and the partner's, the other
+// lane the larger.  With the keys of the second kind of lane held negated, both are min(own, -partner's):
+// two cross-lane moves and one instruction per key instead of a compare and two selects (the selects and the
+// moves issue at the double-precision rate on this chip), plus one xor per key where the convention changes.
+template <int E, int LPB, int J, int SB = 0>
 __device__ __forceinline__ void sort_half_cleaners(double (&c)[E], int q) {
   if constexpr (J >= 1) {
     if constexpr (J < E) {
+      sort_resign<SB, 0>(c, q);
 #pragma unroll
       for (int r = 0; r < E; ++r) {
         const int pr = r ^ J;
         if (pr > r) compare_exchange(c[r], c[pr]);
       }
+      sort_half_cleaners<E, LPB, J / 2, 0>(c, q);
     } else {
       constexpr int lm = J / E;
-      const bool keep_min = (q & lm) == 0;
+      sort_resign<SB, lm>(c, q);
 #pragma unroll
-      for (int r = 0; r < E; ++r) {
-        const double o = lane_xor<lm>(c[r]);
-        c[r] = ((c[r] < o) == keep_min) ? c[r] : o;
-      }
+      for (int r = 0; r < E; ++r) c[r] = min_with_negated(c[r], lane_xor<lm>(c[r]));
       // with 64 keys per lane the scheduler otherwise starts the next stage's exchanges early and spills them
       if constexpr (E >= 64) __builtin_amdgcn_sched_barrier(0);
+      sort_half_cleaners<E, LPB, J / 2, lm>(c, q);
     }
-    sort_half_cleaners<E, LPB, J / 2>(c, q);
+  } else {
+    sort_resign<SB, 0>(c, q);
   }
 }
 
@@ -426,19 +451,20 @@ __device__ __forceinline__ void sort_ascending(double (&c)[E], int q) {
         const int pr = r ^ (K - 1);
         if (pr > r) compare_exchange(c[r], c[pr]);
       }
+      sort_half_cleaners<E, LPB, K / 4, 0>(c, q);
     } else {
-      constexpr int lm = K / E - 1;
-      const bool keep_min = (q & (K / E / 2)) == 0;
+      constexpr int lm = K / E - 1, bit = K / E / 2;
+      sort_resign<0, bit>(c, q);
       // position r meets the partner lane's position E-1-r; two registers at a time keeps this in place
 #pragma unroll
       for (int r = 0; r < E / 2; ++r) {
         const double o_lo = lane_xor<lm>(c[E - 1 - r]), o_hi = lane_xor<lm>(c[r]);
-        c[r] = ((c[r] < o_lo) == keep_min) ? c[r] : o_lo;
-        c[E - 1 - r] = ((c[E - 1 - r] < o_hi) == keep_min) ? c[E - 1 - r] : o_hi;
+        c[r] = min_with_negated(c[r], o_lo);
+        c[E - 1 - r] = min_with_negated(c[E - 1 - r], o_hi);
       }
       if constexpr (E >= 64) __builtin_amdgcn_sched_barrier(0);
+      sort_half_cleaners<E, LPB, K / 4, bit>(c, q);
     }
-    sort_half_cleaners<E, LPB, K / 4>(c, q);
     sort_ascending<E, LPB, K * 2>(c, q);
   }
 }
