@@ -14,9 +14,11 @@
  *     themselves live in HOST memory and are read before the call returns.
  *   - Work is enqueued on `stream` and is NOT synchronised; outputs are valid
  *     once the stream has reached the end of the enqueued work.
- *   - Return value: TSENOR_OK (0) or a negative tsenor_status.  Arguments are
- *     validated on the host before anything is enqueued; on error nothing was
- *     enqueued.  Inputs must be finite; NaN/Inf weights give unspecified masks.
+ *   - Return value: TSENOR_OK (0) or a negative tsenor_status.  Every argument of
+ *     every problem of a call is validated on the host before anything is enqueued:
+ *     on any error but TSENOR_ERR_HIP nothing was enqueued (TSENOR_ERR_HIP reports a
+ *     failing launch, after which earlier launches of the call may already be queued).
+ *     Inputs must be finite; NaN/Inf weights give unspecified masks.
  *   - Matrices are row-major; element (i, j) of W is W[i * ld + j]; the mask and
  *     the optional plan use leading dimension `cols`.
  *   - rows and cols must be multiples of M (the method never pads, Sec. 3.1);
@@ -44,7 +46,8 @@ typedef void* tsenor_stream_t;
 typedef enum tsenor_status {
   TSENOR_OK = 0,
   TSENOR_ERR_NULL = -1,        /* a required pointer is NULL */
-  TSENOR_ERR_SHAPE = -2,       /* rows/cols <= 0, not multiples of M, ld < cols, or too large */
+  TSENOR_ERR_SHAPE = -2,       /* rows/cols <= 0, not multiples of M, ld < cols, or too large (more than 2^40
+                                  weights in a matrix, or 2^31 or more blocks of one size in a call) */
   TSENOR_ERR_NM = -3,          /* N < 0 or N > M */
   TSENOR_ERR_UNSUPPORTED = -4, /* M not in {4, 8, 16, 32, 64}, unknown dtype, tau_mode or flag */
   TSENOR_ERR_PARAM = -5,       /* tau <= 0 or not finite, iters < 0, tau out of the supported range */
@@ -137,8 +140,8 @@ typedef struct tsenor_problem {
   uint8_t* packed_out;    /* device out, rows x cols/8 bytes: bit (j & 7) of byte j >> 3 of row i is S_ij; needs
                              cols % 8 == 0 */
   void* pruned_out;       /* device out, rows x cols elements of W's dtype, leading dimension cols: x_ij where the
-                             mask keeps it, +0 elsewhere ("setting all elements outside the mask to zero", Sec. 4;
-                             the D-update of Proposition 1).  bf16 output rounds x to nearest-even */
+                             mask keeps it, +0 elsewhere (the pruned weights of Sec. 4; the D-update of
+                             Proposition 1).  bf16 output rounds x to nearest-even */
   double* objective_out;  /* device out, 2 doubles: [0] sum_ij S_ij * importance_ij of the returned mask (the
                              objective of Eq. 1), [1] the same for prev_mask (0 if none).  Summed block by block in a
                              fixed order: bitwise reproducible from run to run */
@@ -159,36 +162,32 @@ enum { TSENOR_ADAPTIVE_CHECK_EVERY = 4 };
 enum { TSENOR_IMPORTANCE_ABS = 0, TSENOR_IMPORTANCE_SQUARE = 1 };
 
 /* Bytes of device scratch that tsenor_mask_ex / tsenor_mask_batched need for these problems
- * (the sum over the batch).  0 on invalid arguments. */
+ * (the sum over the batch).  0 on invalid arguments.  The scratch holds what passes between the kernels of
+ * the path: the scan order of Algorithm 2 line 1 (two bytes per weight), the mask greedy selection leaves
+ * (Algorithm 2 line 6) and per-block objective values of Eq. 1. */
 size_t tsenor_workspace_bytes(const tsenor_problem* problems, int count);
 
-/* The whole path (tile load -> Algorithm 1 -> Algorithm 2 -> mask write) for one matrix.
+/* The whole path (tile load -> Algorithm 1 -> Algorithm 2 -> mask write) for one matrix: Eq. 1 solved block
+ * by block (Eq. 2) as in Sec. 3.2 and 3.3.
  * `workspace`: device memory, 256-byte aligned, at least tsenor_workspace_bytes(p, 1) bytes; its contents
  * are scratch.  Calls that overlap in time must not share a workspace. */
 int tsenor_mask_ex(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream);
 
-/* The same for `count` matrices (for example the seven projections of a decoder layer) on one stream.
- * Problems may differ in every field.  Those that share M and the kernel variant (default, fp32 iterations,
- * iters == 0) go through the kernels together, up to 16 matrices per launch: one launch of every kernel
- * serves the whole group.  Results are those of `count` separate tsenor_mask_ex calls, bit for bit. */
+/* The same for `count` matrices (for example the seven projections of a decoder layer) on one stream.  The
+ * problem of Eq. 1 separates into independent blocks (Sec. 3.1, Eq. 2), and so do the blocks of different
+ * matrices: problems may differ in every field, and those that share M and the kernel variant (default, fp32
+ * iterations, iters == 0, tiling, ...) go through the kernels together, up to 16 matrices per launch: one
+ * launch of every kernel serves the whole group.  The kernel variant of a problem is chosen from that problem
+ * alone, so the results are those of `count` separate tsenor_mask_ex calls, bit for bit. */
 int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspace, size_t workspace_bytes,
                         tsenor_stream_t stream);
 
-/* Convenience form of the paper's problem statement: fp32 weights, importance |W|, ld = cols,
- * K = tau * |W| (ABSOLUTE), default local search.  Allocates its scratch with hipMallocAsync on
- * `stream` and frees it with hipFreeAsync; everything else as tsenor_mask_ex. */
+/* Convenience form of the paper's problem statement (Eq. 1; Algorithm 1 and Algorithm 2 with their inputs as
+ * printed): fp32 weights, importance |W|, ld = cols, K = tau * |W| (ABSOLUTE), default local search.
+ * Allocates its scratch with hipMallocAsync on `stream` and frees it with hipFreeAsync; everything else as
+ * tsenor_mask_ex. */
 int tsenor_mask(const float* W, int64_t rows, int64_t cols, int N, int M, float tau, int iters, uint8_t* mask,
                 tsenor_stream_t stream);
-
-/* Measurement aid for benchmarks: runs tsenor_mask_ex `repeats` times (1..4096) back to back on `stream`
- * with HIP events recorded at the stage boundaries, SYNCHRONISES the stream, and writes to the HOST array
- * stage_ms[TSENOR_NUM_STAGES] the mean duration in milliseconds of
- *   [0] workspace reset + matrix maximum (REL_MATRIX_MAX only)   [1] tile load + Algorithm 1 + sort
- *   [2] greedy selection (Algorithm 2 lines 1-6)                 [3] local search + mask write.
- * Outputs are those of the last repeat.  Creates and destroys its events; allocates no device memory. */
-#define TSENOR_NUM_STAGES 4
-int tsenor_mask_ex_profile(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream,
-                           int repeats, float* stage_ms);
 
 const char* tsenor_status_string(int status);
 int tsenor_version(void);

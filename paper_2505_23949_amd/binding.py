@@ -10,11 +10,8 @@ from __future__ import annotations
 import ctypes
 from pathlib import Path
 
-import os
-
 _PKG = Path(__file__).resolve().parent
-# TSENOR_LIBRARY names another build of the same library (for A/B measurements); default is the in-tree one
-LIB_PATH = Path(os.environ.get("TSENOR_LIBRARY", _PKG / "libtsenor.so"))
+LIB_PATH = _PKG / "libtsenor.so"
 
 TSENOR_OK = 0
 TSENOR_ERR_NULL = -1

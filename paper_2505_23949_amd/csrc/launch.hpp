@@ -1,0 +1,54 @@
+// Interface between the host code of the library and the kernels that depend on the block size M.  The
+// kernels of every M are compiled in a translation unit of their own (launch_m4.hip ... launch_m64.hip, all of
+// them instantiating launch_impl.hpp), so that the library builds in parallel.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "problem.hpp"
+
+namespace tsenor_dev {
+
+// kernel variant of a problem: problems with the same variant can share one fused launch
+struct Variant {
+  int M;
+  bool fast, zero_t;
+  uint32_t greedy;  // 0: chosen by size, else the TSENOR_FLAG_GREEDY_* asked for
+  bool small;       // the Dykstra kernel's small tiles (decided per problem, so that fusing never changes results)
+  bool simple;      // TSENOR_FLAG_SIMPLE_ROUNDING
+  bool adaptive;    // tol > 0: the early-exit instantiation of the Dykstra kernel
+  bool operator==(const Variant& o) const {
+    return M == o.M && fast == o.fast && zero_t == o.zero_t && greedy == o.greedy && small == o.small &&
+           simple == o.simple && adaptive == o.adaptive;
+  }
+};
+
+// Below this many blocks in a matrix the Dykstra kernel uses the small tiles (M <= 32, double iterations):
+// with so few waves every SIMD holds at most one, whose iteration time is its instruction count.
+// Measured crossovers (300 iterations of a few blocks, small against large tiles: M = 32: 108 us against 140;
+// M = 16: 91 against 146; M = 8: 46 against 84; M = 4: 35 against 90).
+constexpr int64_t small_tiles_below_blocks(int M) {
+  return M == 4 ? 50000 : M == 8 ? 9000 : M == 16 ? 9000 : M == 32 ? 1500 : 0;
+}
+
+// Below this many blocks in a launch the greedy selection runs with M lanes per block: the one-lane kernel
+// takes the time of M*M dependent steps of a single wave however few blocks there are (22 / 70 / 300 us for
+// M = 16 / 32 / 64), the M-lane kernel issues several times the instructions but its chain is M steps
+// (14 / 23 / 41 us), so it wins while it does not fill the chip.  Measured crossovers; for M <= 8 the
+// one-lane kernel is never slower.
+constexpr int64_t greedy_wide_below_blocks(int M) { return M == 16 ? 2500 : M == 32 ? 7000 : M == 64 ? 16000 : 0; }
+
+// Enqueues the kernels of one fused launch that depend on M: tile load + Algorithm 1 + sort, greedy selection
+// (or the simple rounding arm), local search + mask write.  `b.count` non-degenerate problems of variant v.
+// ev (optional): events recorded after the first and the second of the three.
+// Returns false if a launch could not be described (more workgroups than a grid holds).
+template <int M>
+bool launch_block_kernels(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t ev_sorted, hipEvent_t ev_greedy);
+
+extern template bool launch_block_kernels<4>(Batch&, const Variant&, hipStream_t, hipEvent_t, hipEvent_t);
+extern template bool launch_block_kernels<8>(Batch&, const Variant&, hipStream_t, hipEvent_t, hipEvent_t);
+extern template bool launch_block_kernels<16>(Batch&, const Variant&, hipStream_t, hipEvent_t, hipEvent_t);
+extern template bool launch_block_kernels<32>(Batch&, const Variant&, hipStream_t, hipEvent_t, hipEvent_t);
+extern template bool launch_block_kernels<64>(Batch&, const Variant&, hipStream_t, hipEvent_t, hipEvent_t);
+
+}  // namespace tsenor_dev

@@ -10,9 +10,9 @@
 //                                       per block, for small launches; simple_round_kernel: the ablation arm)
 //                                                                                         [rounding.hpp]
 //   4. finalize_kernel                  Algorithm 2 lines 7-13 (local search), mask write [rounding.hpp]
-//   5. objective_kernel, emit_kernel, stats_kernel   optional outputs
-// Every kernel takes the table of the group by value and finds the matrix of a workgroup from a prefix of
-// workgroup counts.
+//   5. objective_kernel, emit_kernel, stats_kernel   optional outputs                     [outputs.hpp]
+// Steps 2-4 depend on the block size and are compiled per M (launch.hpp).  Every kernel takes the table of
+// the group by value and finds the matrix of a workgroup from a prefix of workgroup counts.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -20,10 +20,12 @@
 #include <cmath>
 #include <vector>
 
-#include "dykstra_sort.hpp"
+#include "lanes.hpp"
+#include "launch.hpp"
+#include "outputs.hpp"
 #include "problem.hpp"
-#include "rounding.hpp"
 #include "tsenor.h"
+#include "tsenor_profile.h"
 
 namespace {
 
@@ -188,40 +190,22 @@ int validate(const tsenor_problem* p) {
 
 inline bool degenerate(const tsenor_problem& p) { return p.N == 0 || p.N == p.M; }
 
-// kernel variant of a problem: problems with the same variant can share one fused launch
-struct Variant {
-  int M;
-  bool fast, zero_t;
-  uint32_t greedy;  // 0: chosen by size, else the TSENOR_FLAG_GREEDY_* asked for
-  uint32_t tiles;   // 0: chosen by size, else the TSENOR_FLAG_TILES_* asked for
-  bool simple;      // TSENOR_FLAG_SIMPLE_ROUNDING
-  bool adaptive;    // tol > 0: the early-exit instantiation of the Dykstra kernel
-  bool operator==(const Variant& o) const {
-    return M == o.M && fast == o.fast && zero_t == o.zero_t && greedy == o.greedy && tiles == o.tiles &&
-           simple == o.simple && adaptive == o.adaptive;
-  }
-};
 inline Variant variant_of(const tsenor_problem& p) {
-  return {p.M, p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0, p.iters == 0,
-          p.flags & (uint32_t)(TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES),
-          p.flags & (uint32_t)(TSENOR_FLAG_TILES_LARGE | TSENOR_FLAG_TILES_SMALL),
-          (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0, p.tol > 0.0 && p.iters > 0};
+  Variant v;
+  v.M = p.M;
+  v.fast = p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0;
+  v.zero_t = p.iters == 0;
+  v.greedy = p.flags & (uint32_t)(TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES);
+  // the tiling is decided from the matrix's own number of blocks, never from what it is fused with: the two
+  // tilings differ in the order of the additions inside a row or column sum
+  const int64_t nblocks = (p.rows / p.M) * (p.cols / p.M);
+  v.small = p.M <= 32 && !v.fast && !v.zero_t &&
+            ((p.flags & TSENOR_FLAG_TILES_SMALL) != 0 ||
+             (!(p.flags & TSENOR_FLAG_TILES_LARGE) && nblocks < small_tiles_below_blocks(p.M)));
+  v.simple = (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0;
+  v.adaptive = p.tol > 0.0 && p.iters > 0;
+  return v;
 }
-
-// Below this many blocks in a launch the Dykstra kernel uses the small tiles (M <= 32, double iterations):
-// with so few waves every SIMD holds at most one, whose iteration time is its instruction count.
-// Measured crossovers (300 iterations of a few blocks, small against large tiles: M = 32: 108 us against 140;
-// M = 16: 91 against 146; M = 8: 46 against 84; M = 4: 35 against 90).
-constexpr int64_t small_tiles_below_blocks(int M) {
-  return M == 4 ? 50000 : M == 8 ? 9000 : M == 16 ? 9000 : M == 32 ? 1500 : 0;
-}
-
-// Below this many blocks in a launch the greedy selection runs with M lanes per block: the one-lane kernel
-// takes the time of M*M dependent steps of a single wave however few blocks there are (22 / 70 / 300 us for
-// M = 16 / 32 / 64), the M-lane kernel issues several times the instructions but its chain is M steps
-// (14 / 23 / 41 us), so it wins while it does not fill the chip.  Measured crossovers; for M <= 8 the
-// one-lane kernel is never slower.
-constexpr int64_t greedy_wide_below_blocks(int M) { return M == 16 ? 2500 : M == 32 ? 7000 : M == 64 ? 16000 : 0; }
 
 BatchEntry entry_of(const tsenor_problem& p, char* ws) {
   const WsLayout l = layout_of(p);
@@ -291,22 +275,13 @@ dim3 strided_grid(const Batch& b, bool vec_only, unsigned target, bool for_absma
   return dim3(gx, gy, (unsigned)b.count);
 }
 
-// prefix of workgroup counts when every matrix gets ceil(units / per_group) workgroups; false on overflow
-bool assign_groups(Batch& b, int64_t (*units)(const BatchEntry&), int64_t per_group) {
-  int64_t total = 0;
-  for (int k = 0; k < b.count; ++k) {
-    b.first[k] = (unsigned)total;
-    total += (units(b.e[k]) + per_group - 1) / per_group;
-    if (total > 0x7FFFFFFF) return false;
-  }
-  for (int k = b.count; k <= kMaxBatch; ++k) b.first[k] = (unsigned)total;
-  return true;
-}
+// A fused launch gives every block at least a lane and at most a workgroup of its own, so its grids hold as
+// long as the blocks of the group number fewer than 2^31.
+constexpr int64_t kMaxBlocksPerLaunch = 0x7FFFFFFF;
 
 // All kernels of one fused launch: `b.count` non-degenerate problems of the same variant.
 // ev (optional): TSENOR_NUM_STAGES + 1 events recorded at the stage boundaries.
-template <int M>
-int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev) {
+int run_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev = nullptr) {
   auto mark = [&](int k) {
     if (ev) (void)hipEventRecord(ev[k], stream);
   };
@@ -322,77 +297,21 @@ int launch_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev)
   init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
   if (any_rel) absmax_kernel<<<strided_grid(b, false, 512, true), 256, 0, stream>>>(b);
   mark(1);
-  constexpr int BPW = kWave >> (Tiling<M>::NX + Tiling<M>::NY);
-  const auto blocks = [](const BatchEntry& e) { return e.p.nblocks; };
-  int64_t total_blocks = 0;
-  for (int k = 0; k < b.count; ++k) total_blocks += b.e[k].p.nblocks;
-  constexpr bool kHasSmall = M <= 32;
-  const bool small = kHasSmall && !v.fast && !v.zero_t &&
-                     (v.tiles ? v.tiles == TSENOR_FLAG_TILES_SMALL : total_blocks < small_tiles_below_blocks(M));
-  if (small) {
-    if constexpr (kHasSmall) {
-      constexpr int BPWS = kWave >> (Tiling<M, true>::NX + Tiling<M, true>::NY);
-      if (v.adaptive) {
-        using L = DykstraLaunch<M, false, true>;
-        if (!assign_groups(b, blocks, (int64_t)BPWS * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
-        dykstra_sort_kernel<M, false, false, true, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
-      } else {
-        using L = DykstraLaunch<M, false>;
-        if (!assign_groups(b, blocks, (int64_t)BPWS * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
-        dykstra_sort_kernel<M, false, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
-      }
-    }
-  } else if (v.fast && v.adaptive) {
-    using L = DykstraLaunch<M, true, true>;
-    if (!assign_groups(b, blocks, (int64_t)BPW * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
-    dykstra_sort_kernel<M, true, false, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
-  } else if (v.fast) {
-    using L = DykstraLaunch<M, true>;
-    if (!assign_groups(b, blocks, (int64_t)BPW * L::kWavesPerGroup)) return TSENOR_ERR_SHAPE;
-    dykstra_sort_kernel<M, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
-  } else {
-    using L = DykstraLaunch<M, false>;
-    using LA = DykstraLaunch<M, false, true>;
-    if (!assign_groups(b, blocks, (int64_t)BPW * (v.adaptive ? LA::kWavesPerGroup : L::kWavesPerGroup)))
-      return TSENOR_ERR_SHAPE;
-    if (v.zero_t)
-      dykstra_sort_kernel<M, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
-    else if (v.adaptive)
-      dykstra_sort_kernel<M, false, false, false, true><<<b.first[b.count], LA::kThreads, 0, stream>>>(b);
-    else
-      dykstra_sort_kernel<M, false><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
+  hipEvent_t ev_sorted = ev ? ev[2] : nullptr, ev_greedy = ev ? ev[3] : nullptr;
+  bool ok = false;
+  switch (v.M) {
+    case 4: ok = launch_block_kernels<4>(b, v, stream, ev_sorted, ev_greedy); break;
+    case 8: ok = launch_block_kernels<8>(b, v, stream, ev_sorted, ev_greedy); break;
+    case 16: ok = launch_block_kernels<16>(b, v, stream, ev_sorted, ev_greedy); break;
+    case 32: ok = launch_block_kernels<32>(b, v, stream, ev_sorted, ev_greedy); break;
+    case 64: ok = launch_block_kernels<64>(b, v, stream, ev_sorted, ev_greedy); break;
   }
-  mark(2);
-  const bool wide = v.greedy ? v.greedy == TSENOR_FLAG_GREEDY_M_LANES : total_blocks < greedy_wide_below_blocks(M);
-  if (v.simple) {
-    if (!assign_groups(b, blocks, kWave)) return TSENOR_ERR_SHAPE;
-    simple_round_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
-  } else if (wide) {
-    if (!assign_groups(b, blocks, kWave / M)) return TSENOR_ERR_SHAPE;
-    greedy_wide_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
-  } else {
-    if (!assign_groups(b, blocks, kWave)) return TSENOR_ERR_SHAPE;
-    greedy_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
-  }
-  mark(3);
-  if (!assign_groups(b, blocks, kWave / M)) return TSENOR_ERR_SHAPE;
-  finalize_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
+  if (!ok) return TSENOR_ERR_SHAPE;  // (ruled out by the checks before the first launch)
   if (any_objective) objective_kernel<<<b.count, 1024, 0, stream>>>(b);
   if (any_emit) emit_kernel<<<strided_grid(b, true, 2048, false), 256, 0, stream>>>(b);
   if (any_stats) stats_kernel<<<1, 4 * kMaxBatch, 0, stream>>>(b);
   mark(4);
   return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
-}
-
-int run_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev = nullptr) {
-  switch (v.M) {
-    case 4: return launch_group<4>(b, v, stream, ev);
-    case 8: return launch_group<8>(b, v, stream, ev);
-    case 16: return launch_group<16>(b, v, stream, ev);
-    case 32: return launch_group<32>(b, v, stream, ev);
-    case 64: return launch_group<64>(b, v, stream, ev);
-  }
-  return TSENOR_ERR_UNSUPPORTED;
 }
 
 // N = 0 and N = M need no solve: the mask is constant and the statistics are zero.
@@ -412,30 +331,9 @@ int run_degenerate(const tsenor_problem& p, char* ws, hipStream_t stream, hipEve
   return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
 }
 
-int run_one(const tsenor_problem& p, char* ws, hipStream_t stream, hipEvent_t* ev = nullptr) {
-  if (degenerate(p)) return run_degenerate(p, ws, stream, ev);
-  Batch b = {};
-  b.count = 1;
-  b.e[0] = entry_of(p, ws);
-  return run_group(b, variant_of(p), stream, ev);
-}
-
-}  // namespace
-
-extern "C" {
-
-size_t tsenor_workspace_bytes(const tsenor_problem* problems, int count) {
-  if (!problems || count <= 0) return 0;
-  size_t total = 0;
-  for (int k = 0; k < count; ++k) {
-    if (validate(&problems[k]) != TSENOR_OK) return 0;
-    total += layout_of(problems[k]).total;
-  }
-  return total;
-}
-
-int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspace, size_t workspace_bytes,
-                        tsenor_stream_t stream) {
+// Everything a call checks before it enqueues anything: every problem on its own, the workspace, and that the
+// fused launches can be described.  `need` receives the workspace bytes of the call.
+int check_call(const tsenor_problem* problems, int count, const void* workspace, size_t workspace_bytes) {
   if (!problems || count <= 0) return TSENOR_ERR_NULL;
   size_t need = 0;
   for (int k = 0; k < count; ++k) {
@@ -445,8 +343,29 @@ int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspa
   }
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) || workspace_bytes < need)
     return TSENOR_ERR_WORKSPACE;
-  char* const base = static_cast<char*>(workspace);
-  hipStream_t s = static_cast<hipStream_t>(stream);
+  // blocks per block size: an upper bound of what any fused launch of the call holds
+  int64_t blocks_of_m[65] = {};
+  for (int k = 0; k < count; ++k) {
+    const tsenor_problem& p = problems[k];
+    if (degenerate(p)) continue;
+    blocks_of_m[p.M] += (p.rows / p.M) * (p.cols / p.M);
+    if (blocks_of_m[p.M] > kMaxBlocksPerLaunch) return TSENOR_ERR_SHAPE;
+  }
+  return TSENOR_OK;
+}
+
+// One checked problem (no host allocation on this path).  Only a failing HIP call can stop it.
+int run_one(const tsenor_problem& p, char* ws, hipStream_t s, hipEvent_t* ev = nullptr) {
+  if (degenerate(p)) return run_degenerate(p, ws, s, ev);
+  Batch b = {};
+  b.count = 1;
+  b.e[0] = entry_of(p, ws);
+  return run_group(b, variant_of(p), s, ev);
+}
+
+// The checked problems of a batch, group by group.  Only a failing HIP call can stop this once it has started.
+int run_checked(const tsenor_problem* problems, int count, char* base, hipStream_t s) {
+  if (count == 1) return run_one(problems[0], base, s);
   // workspace slice of every problem, in the order given
   std::vector<size_t> offset((size_t)count);
   size_t at = 0;
@@ -477,6 +396,27 @@ int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspa
   return TSENOR_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+size_t tsenor_workspace_bytes(const tsenor_problem* problems, int count) {
+  if (!problems || count <= 0) return 0;
+  size_t total = 0;
+  for (int k = 0; k < count; ++k) {
+    if (validate(&problems[k]) != TSENOR_OK) return 0;
+    total += layout_of(problems[k]).total;
+  }
+  return total;
+}
+
+int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspace, size_t workspace_bytes,
+                        tsenor_stream_t stream) {
+  const int rc = check_call(problems, count, workspace, workspace_bytes);
+  if (rc != TSENOR_OK) return rc;
+  return run_checked(problems, count, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
 int tsenor_mask_ex(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream) {
   return tsenor_mask_batched(p, 1, workspace, workspace_bytes, stream);
 }
@@ -484,11 +424,9 @@ int tsenor_mask_ex(const tsenor_problem* p, void* workspace, size_t workspace_by
 int tsenor_mask_ex_profile(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream,
                            int repeats, float* stage_ms) {
   if (!p || !stage_ms) return TSENOR_ERR_NULL;
-  const int rc = validate(p);
+  const int rc = check_call(p, 1, workspace, workspace_bytes);
   if (rc != TSENOR_OK) return rc;
   if (repeats <= 0 || repeats > 4096) return TSENOR_ERR_PARAM;
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) || workspace_bytes < layout_of(*p).total)
-    return TSENOR_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   constexpr int NE = TSENOR_NUM_STAGES + 1;
   hipEvent_t* ev = new hipEvent_t[(size_t)repeats * NE];
@@ -498,7 +436,8 @@ int tsenor_mask_ex_profile(const tsenor_problem* p, void* workspace, size_t work
       out = TSENOR_ERR_HIP;
       break;
     }
-  for (int r = 0; r < repeats && out == TSENOR_OK; ++r) out = run_one(*p, static_cast<char*>(workspace), s, ev + r * NE);
+  for (int r = 0; r < repeats && out == TSENOR_OK; ++r)
+    out = run_one(*p, static_cast<char*>(workspace), s, ev + r * NE);
   if (out == TSENOR_OK && hipStreamSynchronize(s) != hipSuccess) out = TSENOR_ERR_HIP;
   for (int k = 0; k < TSENOR_NUM_STAGES; ++k) stage_ms[k] = 0.0f;
   for (int r = 0; r < repeats && out == TSENOR_OK; ++r)
@@ -533,7 +472,7 @@ int tsenor_mask(const float* W, int64_t rows, int64_t cols, int N, int M, float 
   void* ws = nullptr;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (hipMallocAsync(&ws, bytes, s) != hipSuccess) return TSENOR_ERR_HIP;
-  const int rc2 = run_one(p, static_cast<char*>(ws), s);
+  const int rc2 = tsenor_mask_batched(&p, 1, ws, bytes, stream);
   if (hipFreeAsync(ws, s) != hipSuccess) return TSENOR_ERR_HIP;
   return rc2;
 }
@@ -542,7 +481,7 @@ const char* tsenor_status_string(int status) {
   switch (status) {
     case TSENOR_OK: return "ok";
     case TSENOR_ERR_NULL: return "a required pointer is NULL";
-    case TSENOR_ERR_SHAPE: return "rows/cols must be positive multiples of M, ld >= cols, at most 2^40 weights";
+    case TSENOR_ERR_SHAPE: return "rows/cols must be positive multiples of M, ld >= cols, at most 2^40 weights and fewer than 2^31 blocks of one size per call";
     case TSENOR_ERR_NM: return "N must satisfy 0 <= N <= M";
     case TSENOR_ERR_UNSUPPORTED: return "unsupported M (4, 8, 16, 32, 64), dtype, tau_mode or flag";
     case TSENOR_ERR_PARAM: return "tau must be finite and > 0 (>= 1/690 in REL_MATRIX_MAX mode), iters and local_search_steps >= 0, at most one TSENOR_FLAG_GREEDY_* and one TSENOR_FLAG_TILES_* flag";
@@ -552,6 +491,6 @@ const char* tsenor_status_string(int status) {
   return "unknown status";
 }
 
-int tsenor_version(void) { return 100; }
+int tsenor_version(void) { return 200; }
 
 }  // extern "C"

@@ -100,6 +100,15 @@ CASES = [
     synth.Workload("m32_31of32", 64, 96, 31, 32, 0.01, 60, "f32", "normal", 81),
     synth.Workload("m32_long_run", 64, 96, 16, 32, 0.005, 2000, "f32", "student_t", 85),  # far past convergence
     synth.Workload("m64_long_run", 64, 128, 32, 64, 0.002, 1500, "bf16", "wanda", 86),
+    # the default (double-precision, linear-domain) path near the largest supported log-kernel: K up to 667 and
+    # up to 690 (the documented limit of the relative mode, tau = 1/690)
+    synth.Workload("m16_hard", 128, 128, 8, 16, 0.0015, 300, "f32", "student_t", 84),
+    synth.Workload("m32_hard", 96, 160, 16, 32, 0.0015, 300, "f32", "student_t", 87),
+    synth.Workload("m16_limit", 80, 112, 8, 16, 1.0 / 690.0, 300, "f32", "student_t", 88),
+    synth.Workload("m32_limit", 64, 96, 16, 32, 1.0 / 690.0, 300, "bf16", "wanda", 89),
+    synth.Workload("m64_limit", 64, 128, 32, 64, 1.0 / 690.0, 200, "f32", "student_t", 90),
+    synth.Workload("m8_limit", 48, 72, 4, 8, 1.0 / 690.0, 300, "f32", "student_t", 92),
+    synth.Workload("m4_limit", 36, 52, 2, 4, 1.0 / 690.0, 300, "f32", "student_t", 94),
 ]
 
 
