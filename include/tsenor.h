@@ -52,7 +52,8 @@ typedef enum tsenor_status {
   TSENOR_ERR_UNSUPPORTED = -4, /* M not in {4, 8, 16, 32, 64}, unknown dtype, tau_mode or flag */
   TSENOR_ERR_PARAM = -5,       /* tau <= 0 or not finite, iters < 0, tau out of the supported range */
   TSENOR_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or smaller than tsenor_workspace_bytes */
-  TSENOR_ERR_HIP = -7          /* a HIP call failed; hipGetLastError() holds the cause */
+  TSENOR_ERR_HIP = -7,         /* a HIP call failed; hipGetLastError() holds the cause */
+  TSENOR_ERR_TOO_LARGE = -8    /* tsenor_mask_ex_static only: the problem needs more than TSENOR_STATIC_SCRATCH_BYTES */
 } tsenor_status;
 
 enum { TSENOR_F32 = 0, TSENOR_BF16 = 1 }; /* storage type of W; bf16 is widened exactly */
@@ -188,6 +189,21 @@ int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspa
  * tsenor_mask_ex. */
 int tsenor_mask(const float* W, int64_t rows, int64_t cols, int N, int M, float tau, int iters, uint8_t* mask,
                 tsenor_stream_t stream);
+
+/* tsenor_mask_ex for callers that cannot allocate or pass scratch: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same problems, same kernels, same results; the scratch is a fixed
+ * array of TSENOR_STATIC_SCRATCH_BYTES in device memory that belongs to the library (every GPU the library
+ * runs on holds its own copy from the first call on that GPU until the process ends).  The call allocates
+ * nothing, on the host or on the device, and clears what it needs with a kernel.
+ *   - A problem whose tsenor_workspace_bytes exceeds TSENOR_STATIC_SCRATCH_BYTES is refused with
+ *     TSENOR_ERR_TOO_LARGE before anything is enqueued (the array holds e.g. a 4096 x 4096 matrix with
+ *     M >= 16, or any slab of a column-by-column pruning loop).
+ *   - The array of the CURRENT device is used: `stream` must belong to the current device.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU race (also calls on
+ *     different streams, and replays of graphs that captured such calls).  Order them on one stream or with
+ *     events. */
+#define TSENOR_STATIC_SCRATCH_BYTES (48u << 20)
+int tsenor_mask_ex_static(const tsenor_problem* p, tsenor_stream_t stream);
 
 const char* tsenor_status_string(int status);
 int tsenor_version(void);

@@ -21,6 +21,7 @@ TSENOR_ERR_UNSUPPORTED = -4
 TSENOR_ERR_PARAM = -5
 TSENOR_ERR_WORKSPACE = -6
 TSENOR_ERR_HIP = -7
+TSENOR_ERR_TOO_LARGE = -8
 
 TSENOR_F32 = 0
 TSENOR_BF16 = 1
@@ -39,7 +40,8 @@ TSENOR_IMPORTANCE_ABS = 0
 TSENOR_IMPORTANCE_SQUARE = 1
 
 EXPORTS = (
-    "tsenor_workspace_bytes", "tsenor_mask_ex", "tsenor_mask_batched", "tsenor_mask", "tsenor_mask_ex_profile",
+    "tsenor_workspace_bytes", "tsenor_mask_ex", "tsenor_mask_batched", "tsenor_mask", "tsenor_mask_ex_static",
+    "tsenor_mask_ex_profile",
     "tsenor_status_string", "tsenor_version",
 )
 
@@ -101,6 +103,8 @@ def load() -> ctypes.CDLL:
         lib.tsenor_mask.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                     ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         lib.tsenor_mask.restype = ctypes.c_int
+        lib.tsenor_mask_ex_static.argtypes = [P, ctypes.c_void_p]
+        lib.tsenor_mask_ex_static.restype = ctypes.c_int
         lib.tsenor_mask_ex_profile.argtypes = [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int,
                                                ctypes.POINTER(ctypes.c_float)]
         lib.tsenor_mask_ex_profile.restype = ctypes.c_int
@@ -192,6 +196,16 @@ def tsenor_mask_ex(problem, workspace, stream=None) -> None:
                                workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != TSENOR_OK:
         raise TsenorError(rc, "tsenor_mask_ex")
+
+
+STATIC_SCRATCH_BYTES = 48 << 20
+
+
+def tsenor_mask_ex_static(problem, stream=None) -> None:
+    """tsenor_mask_ex on the library's own fixed scratch (no allocation anywhere in the call)."""
+    rc = load().tsenor_mask_ex_static(ctypes.byref(problem), _stream_handle(stream))
+    if rc != TSENOR_OK:
+        raise TsenorError(rc, "tsenor_mask_ex_static")
 
 
 NUM_STAGES = 4

@@ -20,6 +20,8 @@
 #include <cmath>
 #include <vector>
 
+#include <mutex>
+
 #include "lanes.hpp"
 #include "launch.hpp"
 #include "outputs.hpp"
@@ -396,6 +398,30 @@ int run_checked(const tsenor_problem* problems, int count, char* base, hipStream
   return TSENOR_OK;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Scratch of tsenor_mask_ex_static: a fixed array in device memory, one copy per GPU, held from the moment the
+// library's code is loaded on that GPU until the process ends.  Host code never uses the array's name as an
+// address: the device address is looked up once per device and kept.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[TSENOR_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (nullptr on failure)
+void* static_scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -419,6 +445,18 @@ int tsenor_mask_batched(const tsenor_problem* problems, int count, void* workspa
 
 int tsenor_mask_ex(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream) {
   return tsenor_mask_batched(p, 1, workspace, workspace_bytes, stream);
+}
+
+int tsenor_mask_ex_static(const tsenor_problem* p, tsenor_stream_t stream) {
+  if (!p) return TSENOR_ERR_NULL;
+  const int rc = validate(p);
+  if (rc != TSENOR_OK) return rc;
+  if (layout_of(*p).total > (size_t)TSENOR_STATIC_SCRATCH_BYTES) return TSENOR_ERR_TOO_LARGE;
+  void* ptr = static_scratch_of_current_device();
+  if (!ptr) return TSENOR_ERR_HIP;
+  const int rc2 = check_call(p, 1, ptr, (size_t)TSENOR_STATIC_SCRATCH_BYTES);
+  if (rc2 != TSENOR_OK) return rc2;
+  return run_one(*p, static_cast<char*>(ptr), static_cast<hipStream_t>(stream));
 }
 
 int tsenor_mask_ex_profile(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream,
@@ -487,6 +525,7 @@ const char* tsenor_status_string(int status) {
     case TSENOR_ERR_PARAM: return "tau must be finite and > 0 (>= 1/690 in REL_MATRIX_MAX mode), iters and local_search_steps >= 0, at most one TSENOR_FLAG_GREEDY_* and one TSENOR_FLAG_TILES_* flag";
     case TSENOR_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or smaller than tsenor_workspace_bytes";
     case TSENOR_ERR_HIP: return "a HIP call failed";
+    case TSENOR_ERR_TOO_LARGE: return "tsenor_mask_ex_static: the problem needs more scratch than TSENOR_STATIC_SCRATCH_BYTES; use tsenor_mask_ex with a workspace";
   }
   return "unknown status";
 }
