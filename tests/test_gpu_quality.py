@@ -39,7 +39,8 @@ def _relative_errors(mask, imp, opt, M, feasible=True):
     return (opt - got) / opt
 
 
-@pytest.mark.parametrize("N,M,block_rows,block_cols", [(4, 8, 8, 16), (8, 16, 6, 12), (16, 32, 3, 8)])
+@pytest.mark.parametrize("N,M,block_rows,block_cols", [(2, 4, 16, 32), (4, 8, 8, 16), (8, 16, 6, 12), (16, 32, 3, 8),
+                                                       (32, 64, 2, 3)])
 def test_ablation_arms_against_the_exact_optimum(dev, N, M, block_rows, block_cols):
     import torch
 
@@ -92,6 +93,79 @@ def test_ablation_arms_against_the_exact_optimum(dev, N, M, block_rows, block_co
     assert entropy_optround < direct_optround
     # the full method is close to optimal on these inputs
     assert entropy_optround < 0.01
+
+
+def test_cfg1_relative_error_against_brute_force(dev):
+    # the 2:4 workload at full size: every one of its 16384 blocks against the best of the 90 feasible masks.
+    # The paper prints no number for M = 4 (its figures start at M = 8), so the magnitudes are this build's own
+    # ("parity unpinned"); what is pinned is the sign (a feasible mask never beats the optimum) and that Algorithm 2
+    # with the entropy solution is no worse than greedy selection alone.
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.CONFIGS["cfg1_2of4_512"]
+    g = synth.generate(w)
+    W = torch.from_numpy(g["W_store"]).to(dev)
+    imp = oracle.importance(g["W_f32"], None).astype(np.float64)
+    masks90 = exact.feasible_masks(w.M, w.N)
+    assert len(masks90) == 90
+    blocks = exact.blocks(imp, w.M).reshape(-1, w.M * w.M)
+    opt = (blocks @ masks90.reshape(90, -1).T.astype(np.float64)).max(axis=1)
+    res = binding.solve(W, w.N, w.M, w.tau, w.iters, tau_mode=w.tau_mode)
+    greedy = binding.solve(W, w.N, w.M, w.tau, w.iters, tau_mode=w.tau_mode, local_search_steps=0,
+                           flags=binding.TSENOR_FLAG_STRICT_PAPER)
+    torch.cuda.synchronize()
+    mask = res["mask"].cpu().numpy()
+    assert exact.is_transposable_nm(mask, w.N, w.M)
+    err = _relative_errors(mask, imp, opt, w.M)
+    err_greedy = _relative_errors(greedy["mask"].cpu().numpy(), imp, opt, w.M, feasible=False)
+    optimal = float((err <= 1e-12).mean())
+    print(f"[case] cfg1 2:4, {len(opt)} blocks against brute force: mean relative error {err.mean():.6f}, "
+          f"max {err.max():.4f}, optimal blocks {optimal:.4f}; greedy selection only: mean {err_greedy.mean():.6f}",
+          flush=True)
+    assert err.min() >= -1e-12
+    assert err.mean() <= err_greedy.mean()
+    assert optimal >= 0.9 and err.mean() < 0.005
+
+
+def test_cfg2_relative_error_against_the_lp_on_a_block_sample(dev):
+    # the 8:16 workload at full size: the GPU's mask of every 64th block (1024 blocks) against the exact optimum
+    # of Eq. (3) (the metric of Sec. 5.1 / Fig. 3; the paper's values exist only as curves, so the magnitude is
+    # "parity unpinned" and only the sign and the order of the arms are asserted)
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.CONFIGS["cfg2_8of16_4096"]
+    g = synth.generate(w)
+    W = torch.from_numpy(g["W_store"]).to(dev)
+    res = binding.solve(W, w.N, w.M, w.tau, w.iters, tau_mode=w.tau_mode)
+    greedy = binding.solve(W, w.N, w.M, w.tau, w.iters, tau_mode=w.tau_mode, local_search_steps=0,
+                           flags=binding.TSENOR_FLAG_STRICT_PAPER)
+    direct = binding.solve(W, w.N, w.M, w.tau, 0, tau_mode=w.tau_mode)
+    torch.cuda.synchronize()
+    imp = oracle.importance(g["W_f32"], None).astype(np.float64)
+    pick = np.arange(0, (w.rows // w.M) * (w.cols // w.M), 64)
+    assert len(pick) == 1024
+    imp_b = exact.blocks(imp, w.M)[pick]
+    print(f"[case] cfg2 8:16: exact optimum of {len(pick)} sampled blocks", flush=True)
+    opt = np.array([exact.lp_optimum(b, w.N)[0] for b in imp_b])
+
+    def errors(mask, feasible=True):
+        got = (exact.blocks(mask, w.M)[pick] * imp_b).sum(axis=(1, 2))
+        if feasible:
+            assert np.all(got <= opt * (1 + 1e-7))
+        return (opt - got) / opt
+
+    mask = res["mask"].cpu().numpy()
+    assert exact.is_transposable_nm(mask, w.N, w.M)
+    e_full, e_greedy, e_direct = errors(mask), errors(greedy["mask"].cpu().numpy(), False), \
+        errors(direct["mask"].cpu().numpy())
+    print(f"  mean relative error: entropy + Algorithm 2 {e_full.mean():.6f} (max {e_full.max():.5f}), "
+          f"entropy + greedy only {e_greedy.mean():.6f}, Algorithm 2 on the importance {e_direct.mean():.6f}", flush=True)
+    assert e_full.mean() < e_greedy.mean() and e_full.mean() < e_direct.mean()
+    assert e_full.mean() < 0.01
 
 
 def test_a_converged_plan_rounds_better(dev):
