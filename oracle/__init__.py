@@ -36,14 +36,40 @@ def build(force: bool = False) -> Path:
     return _LIB
 
 
+def build_sanitized() -> Path:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (gcc, -O1, frame pointers kept).
+    Loaded instead of the ordinary build by a process that names it in TSENOR_ORACLE_LIBRARY (and preloads the
+    sanitizer runtimes): how the tests run the pins over instrumented code."""
+    out = _DIR / "libtsenor_oracle_sanitized.so"
+    tmp = out.with_suffix(f".so.tmp{os.getpid()}")
+    subprocess.run(
+        ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+         "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+         "-o", str(tmp), str(_SRC), "-lm"],
+        check=True,
+    )
+    os.replace(tmp, out)
+    return out
+
+
 _lib = None
+
+
+def loaded_library() -> str:
+    """Path of the shared library the oracle calls go to."""
+    _load()
+    return _lib._name
 
 
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(str(_LIB))
+        override = os.environ.get("TSENOR_ORACLE_LIBRARY")
+        if override:
+            lib = ctypes.CDLL(override)
+        else:
+            build()
+            lib = ctypes.CDLL(str(_LIB))
         i64, dbl, i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_int
         p = ctypes.c_void_p
         lib.tsenor_oracle_importance.argtypes = [p, i64, i64, i64, p, p]
