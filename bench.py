@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the transposable N:M mask finder on one MI355X.
 
-One "step" is one pass of the whole hot path (matrix maximum, tile load, all T Dykstra iterations,
-sort, greedy selection, local search, mask write) over the headline workload: transposable 16:32 on a
-4096x14336 bf16 matrix with Wanda-style importance, T = 300, entropy weight 0.005 * max importance.
+One "step" is one pass of the whole hot path (matrix maximum, tile load, all T Dykstra iterations, sort, greedy
+selection, local search, mask write) = one call of tsenor_mask_ex over the headline workload: transposable 16:32
+on a 4096x14336 bf16 matrix with Wanda-style importance, T = 300, entropy weight 0.005 * max importance.
 Inputs are synthetic (seeded) and already resident in HBM when the timed region starts.
 
-Prints ONE JSON line: whole-job throughput in masked weights/s, the roofline of the dominant kernel
-measured with HIP events over the same timed steps, and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line: whole-job throughput in masked weights/s over the timed tsenor_mask_ex calls, the roofline
+of the dominant kernel (its duration from HIP events at the stage boundaries of a second, equally long run of
+the same calls), and the CPU oracle timed on a bounded sample.  `--workload all` measures every configuration,
+writes one such line per configuration into gpurun_out/ and prints the headline one.
 """
 from __future__ import annotations
 
@@ -22,35 +24,87 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 METRIC = "masked weights/s (Dykstra+rounding), 16:32 @4096x14336; % of roofline"
+HEADLINE = "cfg3_16of32_4096x14336"
 
-# Roofline model of the dominant kernel (tile load + Algorithm 1 + sort), the binding unit is the vector
-# ALU: per matrix entry and Dykstra iteration the method needs, in its log-domain statement reduced to
-# one exponential, 5 full-rate fp32 vector operations and 1 transcendental at quarter rate = 9 lane-cycles.
-# Peak: 256 CUs x 64 lanes x 2.4 GHz lane-operations per second (no packed math, no FMA doubling).
-ALGO_LANE_OPS_PER_ELEM_ITER = 9.0
-PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12          # fp64 vector issue rate (16 lanes/clk/SIMD)
-PEAK_TLANEOPS_FP32 = 2 * PEAK_TLANEOPS           # fp32 vector issue rate (32 lanes/clk/SIMD; 157.3 TFLOP/s with FMA)
+# ---- roofline of the dominant kernel (tile load + Algorithm 1 + sort): bound by vector-ALU issue ---------------
+# Useful work: the double-precision vector operations per matrix entry and Dykstra iteration that the
+# linear-domain form of Algorithm 1 needs: capped entry (multiply with clamp), row-sum add, column-sum multiply-add,
+# row rescale of the entry = 4 (a multiply-add counts once: it is one issue slot).  The 64 x 64 kernel cannot keep
+# the capped entries in registers and computes them twice: 5.
+# Peak: one double-precision wave instruction per SIMD every 4 cycles = 16 lanes/clk/SIMD:
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.32 T lane-operations/s (the published 78.6 TFLOP/s counts every
+# operation as a multiply-add, i.e. twice).
+PEAK_F64_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# Single-precision iterations (TSENOR_FLAG_FP32_ITERATIONS): packed fp32 instructions are not used, and the rate
+# measured on this chip for plain v_mul_f32 / v_add_f32 / v_fma_f32 is 48-57 T lane-operations/s
+# (profiles/issue_rates_mi355x.md); the upper end is taken as the peak.
+PEAK_F32_PLAIN_TLANEOPS = 57.0
+# The survey's model of the method (5 full-rate vector operations + 1 quarter-rate exponential per entry and
+# iteration = 9 lane-cycles), kept only as a comparison figure: this kernel has no transcendental in its loop.
+SURVEY_MODEL_LANE_OPS = 9.0
 
 
-def recorded_traffic(workload: str, fp32: bool):
-    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-    (scaled by a copy kernel of known size); the figure is kept in the committed profile summary."""
-    if fp32:
-        return None
+def useful_ops_per_entry_iter(M: int) -> float:
+    return 5.0 if M == 64 else 4.0
+
+
+# Vector instructions the compiled default-mode iteration loop issues per wave and iteration, and the matrix
+# entries a wave holds (counted in the ISA of the built library, `v_*` lines between the loop label and its
+# branch; cross-lane ds_swizzle and LDS accesses issue on another pipeline and are not counted).  Keyed by
+# (M, small tiles).
+LOOP_VALU_PER_WAVE_ITER = {
+    (32, False): (169, 2048),
+}
+# a matrix with fewer blocks than this runs the small-tile instantiation (the library's own choice, mirrored here
+# only to pick the row of the table above)
+SMALL_TILES_BELOW_BLOCKS = {4: 50000, 8: 9000, 16: 9000, 32: 1500, 64: 0}
+
+
+def recorded_traffic(workload: str):
+    """HBM bytes of the dominant kernel and of the whole pass, per launch, as recorded in the committed
+    rocprofv3 summary of this workload (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size;
+    not measured in this run)."""
+    out = {"kernel": None, "pass": None}
     path = os.path.join(ROOT, "profiles", f"all_kernels_{workload}.md")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch dykstra_sort_kernel"):
-                return int(line.split(":")[1])
+                out["kernel"] = int(line.split(":")[1])
+            if line.startswith("traffic_bytes_per_pass"):
+                out["pass"] = int(line.split(":")[1])
     except OSError:
         pass
-    return None
+    return out
 
 
-def bench_layer(args) -> int:
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def timed_calls(torch, fn, steps):
+    """`steps` calls of fn enqueued back to back, bracketed by a device synchronisation on both sides.
+    Returns (wall ms per step, HIP-event ms per step on the current stream)."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return wall, start.elapsed_time(stop) / steps
+
+
+def bench_layer(args):
     """Secondary workload: the seven projection matrices of one 8B decoder layer (fp32, 16:32, Wanda-style
     importance) through ONE tsenor_mask_batched call per step.  Wall-clock only (no per-kernel split)."""
-    import numpy as np
     import torch
 
     from paper_2505_23949_amd import binding, synth
@@ -70,17 +124,13 @@ def bench_layer(args) -> int:
     work = torch.empty(binding.tsenor_workspace_bytes(probs), dtype=torch.uint8, device=dev)
     for _ in range(args.warmup):
         binding.tsenor_mask_batched(probs, work)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        binding.tsenor_mask_batched(probs, work)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step, ms_events = timed_calls(torch, lambda: binding.tsenor_mask_batched(probs, work), args.steps)
     weights = sum(w.rows * w.cols for w in ws)
-    out = {
+    return {
         "metric": "masked weights/s (Dykstra+rounding), 16:32, one 8B decoder layer per batched call",
         "value": round(weights / (ms_per_step * 1e-3), 1), "unit": "masked weights/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_hip_events": round(ms_events, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if args.fp32_iterations else "f64",
         "data": "synthetic",
         "config": {"workload": "cfg4_layer", "matrices": [[w.rows, w.cols] for w in ws], "weights": weights,
@@ -88,59 +138,70 @@ def bench_layer(args) -> int:
                    "importance": "wanda", **({"tol": args.tol} if args.tol > 0.0 else {})},
         "roofline": None, "cpu_baseline": None,
     }
-    print(json.dumps(out), flush=True)
-    return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3_16of32_4096x14336")
-    ap.add_argument("--rows", type=int, default=0, help="override rows (debug)")
-    ap.add_argument("--cols", type=int, default=0, help="override cols (debug)")
-    ap.add_argument("--iters", type=int, default=-1, help="override the iteration count T (debug)")
-    ap.add_argument("--absolute-tau", action="store_true",
-                    help="secondary line: K = tau * importance as Algorithm 1 prints it, with the workload's "
-                         "coefficient as tau (no matrix-maximum pre-pass; a nearly flat kernel)")
-    ap.add_argument("--tol", type=float, default=0.0,
-                    help="early exit of the iterations (tsenor_problem.tol); not the headline configuration, the "
-                         "CPU baseline and the fp32 mode are skipped with it")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=4096,
-                    help="rows of the matrix the CPU oracle is timed on (default: the whole headline matrix, ~10 s)")
-    ap.add_argument("--fp32-iterations", action="store_true",
-                    help="time the TSENOR_FLAG_FP32_ITERATIONS mode (iterations after the eighth in fp32)")
-    ap.add_argument("--no-fp32-mode", action="store_true",
-                    help="skip the secondary timing of the fp32-iteration mode (for profiling runs)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one elementwise pass over 256 MiB (reads 256 MiB, writes 256 MiB): the "
-                         "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (blocks are independent; see DESIGN.md for how the "
-              "path would shard); run with --gpus 1", file=sys.stderr)
-        return 2
-
+def bench_slab_loop(args):
+    """Secondary workload, the call shape of a column-by-column pruning loop (Sec. 4, SparseGPT integration): the
+    headline matrix taken M columns at a time, cols/M dependent tsenor_mask_ex calls of a rows x M slab each on
+    one stream (here every slab is solved under its own matrix maximum)."""
     import numpy as np
     import torch
 
     from paper_2505_23949_amd import binding, synth
 
-    binding.load()
-    if args.workload == "cfg4_layer":
-        return bench_layer(args)
-    w = synth.CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    w = synth.CONFIGS[HEADLINE]
+    g = synth.generate(w)
+    W = torch.from_numpy(g["W_store"].view(np.int16)).to(dev).view(torch.bfloat16)
+    cs = torch.from_numpy(g["col_scale"]).to(dev)
+    mask = torch.empty(W.shape, dtype=torch.uint8, device=dev)
+    nslabs = w.cols // w.M
+    probs = []
+    for k in range(nslabs):
+        sl = slice(k * w.M, (k + 1) * w.M)
+        # the mask slab is a strided view: the library writes masks with leading dimension `cols` of the problem,
+        # so every slab gets a contiguous buffer of its own
+        probs.append((W[:, sl], cs[sl]))
+    slab_masks = torch.empty((nslabs, w.rows, w.M), dtype=torch.uint8, device=dev)
+    plist = [binding.make_problem(Wk, w.N, w.M, w.tau, w.iters, mask=slab_masks[k], col_scale=ck,
+                                  tau_mode=w.tau_mode) for k, (Wk, ck) in enumerate(probs)]
+    work = torch.empty(binding.tsenor_workspace_bytes([plist[0]]), dtype=torch.uint8, device=dev)
+
+    def one_pass():
+        for p in plist:
+            binding.tsenor_mask_ex(p, work)
+
+    for _ in range(max(args.warmup // 2, 1)):
+        one_pass()
+    steps = max(args.steps // 4, 1)
+    ms_per_step, ms_events = timed_calls(torch, one_pass, steps)
+    weights = w.rows * w.cols
+    return {
+        "metric": f"masked weights/s, {w.N}:{w.M}, {nslabs} dependent calls of a {w.rows}x{w.M} slab",
+        "value": round(weights / (ms_per_step * 1e-3), 1), "unit": "masked weights/s", "n_gpus": 1,
+        "steps": steps, "warmup": max(args.warmup // 2, 1), "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_hip_events": round(ms_events, 4), "ms_per_call": round(ms_per_step / nslabs, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "slab_loop", "rows": w.rows, "cols": w.cols, "N": w.N, "M": w.M, "iters": w.iters,
+                   "tau": w.tau, "tau_mode": "rel_matrix_max (per slab)", "storage": w.dtype, "importance": w.dist,
+                   "calls_per_step": nslabs},
+        "roofline": None, "cpu_baseline": None,
+    }
+
+
+def bench_matrix(args, name):
+    import numpy as np
+    import torch
+    from dataclasses import replace
+
+    from paper_2505_23949_amd import binding, synth
+
+    w = synth.CONFIGS[name]
     if args.rows and args.cols:
         w = w.scaled(args.rows, args.cols)
     if args.iters >= 0:
-        from dataclasses import replace
-
         w = replace(w, iters=args.iters)
     if args.absolute_tau:
-        from dataclasses import replace
-
         w = replace(w, tau_mode=synth.TAU_ABSOLUTE)
     dev = torch.device("cuda:0")
     g = synth.generate(w)
@@ -153,12 +214,16 @@ def main() -> int:
     stats = torch.zeros(4, dtype=torch.int64, device=dev)
     flags = binding.TSENOR_FLAG_FP32_ITERATIONS if args.fp32_iterations else 0
     iters_done = None
+    no_cpu, no_modes = args.no_cpu_baseline, args.no_other_modes
     if args.tol > 0.0:
-        args.no_cpu_baseline = args.no_fp32_mode = True
+        no_cpu = no_modes = True
         iters_done = torch.zeros((w.rows // w.M) * (w.cols // w.M), dtype=torch.int32, device=dev)
     prob = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask, col_scale=cs, tau_mode=w.tau_mode,
                                 flags=flags, stats_out=stats, tol=args.tol, iters_done_out=iters_done)
     work = torch.empty(binding.tsenor_workspace_bytes([prob]), dtype=torch.uint8, device=dev)
+    weights = w.rows * w.cols
+    nblocks = weights // (w.M * w.M)
+    steps = args.steps
 
     if args.calibrate_copy:
         ref_in = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
@@ -167,119 +232,141 @@ def main() -> int:
         torch.cuda.synchronize()
         del ref_in, ref_out
 
-    for _ in range(args.warmup):
-        binding.tsenor_mask_ex(prob, work)
-    torch.cuda.synchronize()
-    # timed region: exactly `steps` passes, enqueued back to back on the current stream with HIP events at
-    # the stage boundaries; the call synchronises the stream before it returns
-    t0 = time.perf_counter()
-    stage_ms = binding.tsenor_mask_ex_profile(prob, work, args.steps)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    weights = w.rows * w.cols
-    value = weights / (ms_per_step * 1e-3)
-
-    dyk_ms = stage_ms[1]
-    achieved = ALGO_LANE_OPS_PER_ELEM_ITER * weights * w.iters / (dyk_ms * 1e-3) / 1e12
-    peak = PEAK_TLANEOPS_FP32 if args.fp32_iterations else PEAK_TLANEOPS
-    roofline = {
-        "bound": "alu", "kernel": "dykstra_sort_kernel", "achieved": round(achieved, 3),
-        "peak": round(peak, 3), "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-        "traffic": recorded_traffic(w.name, args.fp32_iterations), "kernel_ms": round(dyk_ms, 4),
-        "note": "bound by vector-ALU issue, not memory: ops = lane-operations of the 5 full-rate + 1 quarter-rate "
-                "(exp) per entry and iteration model = 9; peak = 256 CUs x 64 lanes x 2.4 GHz (fp64 vector issue; "
-                "twice that in fp32 mode); the kernel issues ~6 instructions per entry and iteration, so frac can "
-                "exceed 1; traffic = rocprofv3 FETCH_SIZE+WRITE_SIZE bytes per launch recorded in profiles/",
-        "stage_ms": {n: round(v, 4) for n, v in zip(binding.STAGE_NAMES, stage_ms)},
-    }
-    if w.M == 32 and not args.fp32_iterations and w.iters > 0:
-        # second view of the same measurement: vector instructions the loop issues (169 per wave of two
-        # blocks and iteration, counted in the compiled kernel) against the issue slots of the chip at its peak
-        # clock (1024 SIMDs, one double-precision wave instruction per 4 cycles, 2.4 GHz)
-        issued = 169.0 * (weights / 2048.0) * w.iters
-        roofline["loop_issue_frac_of_peak_clock"] = round(issued / (1024 * (dyk_ms * 1e-3) * 2.4e9 / 4.0), 4)
-
-    # host copy of the result for the sample check below
-    mask_host = mask.cpu().numpy()
-
-    other_mode = None
-    if not args.fp32_iterations and not args.no_fp32_mode:
-        # the optional fp32-iteration mode on the same input, same number of steps, reported beside the headline
-        mask32 = torch.empty_like(mask)
-        prob32 = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask32, col_scale=cs, tau_mode=w.tau_mode,
-                                      flags=binding.TSENOR_FLAG_FP32_ITERATIONS)
+    def measure(problem):
+        """(wall ms per tsenor_mask_ex call, the same by HIP events, per-stage ms of a second run, clock MHz)"""
         for _ in range(args.warmup):
-            binding.tsenor_mask_ex(prob32, work)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        stage32 = binding.tsenor_mask_ex_profile(prob32, work, args.steps)
-        torch.cuda.synchronize()
-        ms32 = (time.perf_counter() - t0) * 1e3 / args.steps
-        diff = (mask32 != mask).view(w.rows // w.M, w.M, w.cols // w.M, w.M).any(dim=3).any(dim=1)
-        other_mode = {
-            "flag": "TSENOR_FLAG_FP32_ITERATIONS", "dtype": "f32", "value": round(weights / (ms32 * 1e-3), 1),
-            "ms_per_step": round(ms32, 4), "kernel_ms": round(stage32[1], 4),
-            "frac_of_fp32_peak": round(ALGO_LANE_OPS_PER_ELEM_ITER * weights * w.iters / (stage32[1] * 1e-3) / 1e12
-                                       / PEAK_TLANEOPS_FP32, 4),
-            "blocks_identical_to_default_mode": round(1.0 - float(diff.float().mean()), 6),
-        }
-        del mask32
+            binding.tsenor_mask_ex(problem, work)
+        wall, by_events = timed_calls(torch, lambda: binding.tsenor_mask_ex(problem, work), steps)
+        stage, mhz = binding.tsenor_mask_ex_profile(problem, work, steps, want_clock=True)
+        return wall, by_events, stage, mhz
 
-    early_exit = early_exit32 = None
-    if not args.fp32_iterations and not args.no_fp32_mode and args.tol == 0.0:
-        # the optional early exit (iteration count as a bound) on the same input, reported beside the headline:
-        # with double-precision iterations, and combined with the fp32-iteration mode
-        def early_exit_run(tol, extra_flags, dtype):
-            mask_e = torch.empty_like(mask)
-            done_e = torch.zeros((w.rows // w.M) * (w.cols // w.M), dtype=torch.int32, device=dev)
-            prob_e = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask_e, col_scale=cs,
-                                          tau_mode=w.tau_mode, tol=tol, iters_done_out=done_e, flags=extra_flags)
-            for _ in range(args.warmup):
-                binding.tsenor_mask_ex(prob_e, work)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            stage_e = binding.tsenor_mask_ex_profile(prob_e, work, args.steps)
-            torch.cuda.synchronize()
-            ms_e = (time.perf_counter() - t0) * 1e3 / args.steps
-            diff = (mask_e != mask).view(w.rows // w.M, w.M, w.cols // w.M, w.M).any(dim=3).any(dim=1)
-            return {
-                "tol": tol, "dtype": dtype, "value": round(weights / (ms_e * 1e-3), 1), "ms_per_step": round(ms_e, 4),
-                "kernel_ms": round(stage_e[1], 4), "mean_iterations": round(float(done_e.float().mean()), 1),
-                "blocks_identical_to_default_mode": round(1.0 - float(diff.float().mean()), 6),
-            }
+    # ---- timed region: exactly `steps` calls of tsenor_mask_ex, enqueued back to back on the current stream
+    ms_per_step, ms_events, stage_ms, clock_mhz = measure(prob)
+    value = weights / (ms_per_step * 1e-3)
+    dyk_ms = stage_ms[1]
+    fp32 = args.fp32_iterations
+    entry_iters = float(weights) * w.iters
+    ops = useful_ops_per_entry_iter(w.M)
+    achieved = ops * entry_iters / (dyk_ms * 1e-3) / 1e12
+    peak = PEAK_F32_PLAIN_TLANEOPS if fp32 else PEAK_F64_TLANEOPS
+    traffic = recorded_traffic(w.name) if not fp32 and not (args.rows or args.absolute_tau or args.tol) else \
+        {"kernel": None, "pass": None}
+    esize = 2 if w.dtype == "bf16" else 4
+    roofline = {
+        "bound": "alu", "kernel": f"dykstra_sort_kernel<{w.M}>", "achieved": round(achieved, 3),
+        "peak": round(peak, 3), "unit": "T lane-ops/s", "frac": round(achieved / peak, 4),
+        "traffic": traffic["kernel"], "kernel_ms": round(dyk_ms, 4),
+        "useful_ops_per_entry_iteration": ops,
+        "note": ("bound by vector-ALU issue, not memory. achieved = useful vector operations (a multiply-add is "
+                 "one) x rows x cols x T / kernel time, kernel time from HIP events at the stage boundaries of "
+                 f"{steps} back-to-back passes; peak = "
+                 + ("the rate measured on this chip for plain (unpacked) fp32 multiplies and adds"
+                    if fp32 else "256 CUs x 4 SIMDs x 16 lanes/clk x 2.4 GHz, the fp64 vector issue rate")
+                 + "; traffic = HBM bytes per launch recorded in profiles/ (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE), "
+                   "not measured in this run"),
+        "stage_ms": {n: round(v, 4) for n, v in zip(binding.STAGE_NAMES, stage_ms)},
+        "staged_ms_per_step": round(sum(stage_ms), 4),
+        "shader_clock_mhz_in_loop": round(clock_mhz, 1),
+        "vs_survey_9op_model": round(SURVEY_MODEL_LANE_OPS * entry_iters / (dyk_ms * 1e-3) / 1e12 / peak, 4),
+        "algorithmic_bytes_per_pass": weights * (esize + 1) + (0 if cs is None else 4 * w.cols),
+        "pass_traffic_recorded_in_profiles": traffic["pass"],
+    }
+    if traffic["pass"]:
+        roofline["pass_traffic_over_algorithmic"] = round(traffic["pass"] / roofline["algorithmic_bytes_per_pass"], 2)
+    if not fp32 and w.iters > 0 and args.tol == 0.0:
+        small = nblocks < SMALL_TILES_BELOW_BLOCKS[w.M]
+        counted = LOOP_VALU_PER_WAVE_ITER.get((w.M, small))
+        if counted:
+            # second view of the same measurement: the vector instructions the loop issues against the issue
+            # slots of the chip (1024 SIMDs, one double-precision wave instruction per 4 cycles), at the peak
+            # clock and at the clock the kernel's first wave saw
+            per_wave, entries = counted
+            issued = per_wave * (weights / entries) * w.iters
+            roofline["loop_valu_per_wave_iteration"] = per_wave
+            roofline["loop_issue_frac_of_peak_clock"] = round(issued / (1024 * (dyk_ms * 1e-3) * 2.4e9 / 4.0), 4)
+            if clock_mhz > 0:
+                roofline["loop_issue_frac_of_held_clock"] = round(
+                    issued / (1024 * (dyk_ms * 1e-3) * clock_mhz * 1e6 / 4.0), 4)
 
-        early_exit = early_exit_run(1e-5, 0, "f64")
-        early_exit32 = early_exit_run(1e-5, binding.TSENOR_FLAG_FP32_ITERATIONS, "f32")
+    mask_host = mask.cpu().numpy()          # host copy of the result for the check against the oracle below
     stats_host = stats.cpu().numpy().tolist()
 
+    other_mode = early_exit = early_exit32 = None
+    if not fp32 and not no_modes:
+        def side_run(tol, extra_flags, dtype):
+            """An optional mode of the library on the same input, same number of steps, reported beside the headline"""
+            mask_e = torch.empty_like(mask)
+            done_e = torch.zeros(nblocks, dtype=torch.int32, device=dev)
+            prob_e = binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=mask_e, col_scale=cs,
+                                          tau_mode=w.tau_mode, tol=tol, iters_done_out=done_e, flags=extra_flags)
+            ms_e, _, stage_e, _ = measure(prob_e)
+            diff = (mask_e != mask).view(w.rows // w.M, w.M, w.cols // w.M, w.M).any(dim=3).any(dim=1)
+            out = {
+                "dtype": dtype, "value": round(weights / (ms_e * 1e-3), 1), "ms_per_step": round(ms_e, 4),
+                "kernel_ms": round(stage_e[1], 4),
+                "blocks_identical_to_default_mode": round(1.0 - float(diff.float().mean()), 6),
+            }
+            if tol > 0.0:
+                out["tol"] = tol
+                out["mean_iterations"] = round(float(done_e.float().mean()), 1)
+            elif dtype == "f32":
+                out["flag"] = "TSENOR_FLAG_FP32_ITERATIONS"
+                out["frac_of_measured_plain_fp32_rate"] = round(
+                    ops * entry_iters / (stage_e[1] * 1e-3) / 1e12 / PEAK_F32_PLAIN_TLANEOPS, 4)
+            return out
+
+        other_mode = side_run(0.0, binding.TSENOR_FLAG_FP32_ITERATIONS, "f32")
+        if args.tol == 0.0:
+            early_exit = side_run(1e-5, 0, "f64")
+            early_exit32 = side_run(1e-5, binding.TSENOR_FLAG_FP32_ITERATIONS, "f32")
+
     cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if not no_cpu:
         import oracle
 
-        rows_s = min(args.cpu_sample_rows, w.rows) // w.M * w.M
         imp = oracle.importance(g["W_f32"], g["col_scale"])
         te = oracle.tau_eff(imp, w.tau, w.tau_mode)       # the matrix maximum is taken over the whole matrix
-        imp_s = np.ascontiguousarray(imp[:rows_s])
-        t0 = time.perf_counter()
-        log_S = oracle.dykstra(imp_s, w.N, w.M, te, w.iters)
-        m_ref, _ = oracle.round_plan(log_S, imp_s, w.N, w.M)
-        cpu_s = time.perf_counter() - t0
-        same = bool(np.array_equal(m_ref, mask_host[:rows_s]))
+        nthreads = oracle.num_threads()
+
+        def cpu_leg(rows_s, threads):
+            oracle.set_threads(threads)
+            imp_s = np.ascontiguousarray(imp[:rows_s])
+            t0 = time.perf_counter()
+            log_S = oracle.dykstra(imp_s, w.N, w.M, te, w.iters)
+            m_ref, _ = oracle.round_plan(log_S, imp_s, w.N, w.M)
+            secs = time.perf_counter() - t0
+            return secs, bool(np.array_equal(m_ref, mask_host[:rows_s]))
+
+        # bounded samples: about 10 s on all threads and about 10 s on one (the oracle does ~6.4e6 weights/s on
+        # 16 threads and ~4.2e5 on one thread for the 16:32 workload; the other block sizes are within 2x)
+        per_weight = max(w.iters, 1) / 300.0
+        rows_all = max(w.M, min(w.rows, int(6.0e7 / per_weight / w.cols) // w.M * w.M))
+        rows_one = max(w.M, min(w.rows, int(3.7e6 / per_weight / w.cols) // w.M * w.M))
+        if args.cpu_sample_rows:
+            rows_all = max(w.M, min(w.rows, args.cpu_sample_rows // w.M * w.M))
+        secs_all, same_all = cpu_leg(rows_all, nthreads)
+        secs_one, same_one = cpu_leg(rows_one, 1)
+        oracle.set_threads(nthreads)
         cpu_baseline = {
-            "value": round(rows_s * w.cols / cpu_s, 1), "unit": "masked weights/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": f"first {rows_s} rows of the {w.rows}x{w.cols} matrix "
-                                        f"({rows_s * w.cols} weights, {cpu_s:.1f} s), tau_eff from the whole matrix",
-            "gpu_mask_equals_oracle_on_sample": same,
+            "value": round(rows_all * w.cols / secs_all, 1), "unit": "masked weights/s", "cores": nthreads,
+            "kind": "oracle",
+            "sample": f"first {rows_all} rows of the {w.rows}x{w.cols} matrix ({rows_all * w.cols} weights, "
+                      f"{secs_all:.1f} s on {nthreads} threads), tau_eff from the whole matrix",
+            "one_thread": {"value": round(rows_one * w.cols / secs_one, 1), "cores": 1,
+                           "sample": f"first {rows_one} rows ({rows_one * w.cols} weights, {secs_one:.1f} s)"},
+            "cpu_model": cpu_model(), "host_cpus_visible": os.cpu_count(),
+            "compiler": "gcc -O2 -std=c99 -fopenmp, no fast-math; OpenMP over blocks",
+            "gpu_mask_equals_oracle_on_sample": same_all and same_one,
         }
 
-    out = {
-        "metric": METRIC if w.name == "cfg3_16of32_4096x14336" and (w.rows, w.cols) == (4096, 14336)
-        and not args.absolute_tau else
+    headline = w.name == HEADLINE and (w.rows, w.cols) == (4096, 14336) and not args.absolute_tau
+    return {
+        "metric": METRIC if headline else
         f"masked weights/s (Dykstra+rounding), {w.N}:{w.M} @{w.rows}x{w.cols}; % of roofline",
-        "value": round(value, 1), "unit": "masked weights/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32" if args.fp32_iterations else "f64", "data": "synthetic",
+        "value": round(value, 1), "unit": "masked weights/s", "n_gpus": 1, "steps": steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "ms_per_step_hip_events": round(ms_events, 4),
+        "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if fp32 else "f64", "data": "synthetic",
         "config": {"workload": w.name, "rows": w.rows, "cols": w.cols, "N": w.N, "M": w.M, "iters": w.iters,
                    "tau": w.tau, "tau_mode": "rel_matrix_max" if w.tau_mode else "absolute",
                    "storage": w.dtype, "importance": w.dist, "rounding_stats": stats_host,
@@ -288,7 +375,64 @@ def main() -> int:
         "roofline": roofline, "cpu_baseline": cpu_baseline, "fp32_iterations_mode": other_mode,
         "early_exit_mode": early_exit, "early_exit_fp32_mode": early_exit32,
     }
-    print(json.dumps(out), flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=HEADLINE,
+                    help="a configuration name, cfg4_layer, slab_loop, or all (one line per configuration into "
+                         "gpurun_out/, the headline line on stdout)")
+    ap.add_argument("--rows", type=int, default=0, help="override rows (debug)")
+    ap.add_argument("--cols", type=int, default=0, help="override cols (debug)")
+    ap.add_argument("--iters", type=int, default=-1, help="override the iteration count T (debug)")
+    ap.add_argument("--absolute-tau", action="store_true",
+                    help="secondary line: K = tau * importance as Algorithm 1 prints it, with the workload's "
+                         "coefficient as tau (no matrix-maximum pre-pass; a nearly flat kernel)")
+    ap.add_argument("--tol", type=float, default=0.0,
+                    help="early exit of the iterations (tsenor_problem.tol); not the headline configuration, the "
+                         "CPU baseline and the other modes are skipped with it")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=0,
+                    help="rows of the matrix the CPU oracle is timed on with all threads (default: sized for ~10 s)")
+    ap.add_argument("--fp32-iterations", action="store_true",
+                    help="time the TSENOR_FLAG_FP32_ITERATIONS mode (iterations after the eighth in fp32)")
+    ap.add_argument("--no-other-modes", "--no-fp32-mode", dest="no_other_modes", action="store_true",
+                    help="skip the secondary timings of the optional modes (for profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one elementwise pass over 256 MiB (reads 256 MiB, writes 256 MiB): the "
+                         "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (blocks are independent; see DESIGN.md for how the "
+              "path would shard); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    from paper_2505_23949_amd import binding, synth
+
+    binding.load()
+
+    def run(name):
+        if name == "cfg4_layer":
+            return bench_layer(args)
+        if name == "slab_loop":
+            return bench_slab_loop(args)
+        return bench_matrix(args, name)
+
+    if args.workload == "all":
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        headline = None
+        for name in [n for n in synth.CONFIGS if n != HEADLINE] + ["cfg4_layer", "slab_loop", HEADLINE]:
+            print(f"bench.py: {name}", file=sys.stderr, flush=True)
+            out = run(name)
+            with open(os.path.join(ROOT, "gpurun_out", f"bench_{name}.json"), "w") as fh:
+                fh.write(json.dumps(out) + "\n")
+            headline = out
+        print(json.dumps(headline), flush=True)
+    else:
+        print(json.dumps(run(args.workload)), flush=True)
     return 0
 
 

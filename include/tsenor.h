@@ -52,7 +52,7 @@ typedef enum tsenor_status {
   TSENOR_ERR_UNSUPPORTED = -4, /* M not in {4, 8, 16, 32, 64}, unknown dtype, tau_mode or flag */
   TSENOR_ERR_PARAM = -5,       /* tau <= 0 or not finite, iters < 0, tau out of the supported range */
   TSENOR_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or smaller than tsenor_workspace_bytes */
-  TSENOR_ERR_HIP = -7,         /* a HIP call failed; hipGetLastError() holds the cause */
+  TSENOR_ERR_HIP = -7,         /* a HIP call failed; tsenor_last_hip_error() returns the runtime's error code */
   TSENOR_ERR_TOO_LARGE = -8    /* tsenor_mask_ex_static only: the problem needs more than TSENOR_STATIC_SCRATCH_BYTES */
 } tsenor_status;
 
@@ -204,6 +204,11 @@ int tsenor_mask(const float* W, int64_t rows, int64_t cols, int N, int M, float 
  *     events. */
 #define TSENOR_STATIC_SCRATCH_BYTES (48u << 20)
 int tsenor_mask_ex_static(const tsenor_problem* p, tsenor_stream_t stream);
+
+/* The hipError_t value of the last HIP failure that a call made by THIS thread reported as TSENOR_ERR_HIP
+ * (0 if there was none).  A launch fails, for example, when the pointers or the stream of a call come from
+ * another copy of the HIP runtime than the one this library is linked to. */
+int tsenor_last_hip_error(void);
 
 const char* tsenor_status_string(int status);
 int tsenor_version(void);

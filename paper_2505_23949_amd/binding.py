@@ -41,7 +41,7 @@ TSENOR_IMPORTANCE_SQUARE = 1
 
 EXPORTS = (
     "tsenor_workspace_bytes", "tsenor_mask_ex", "tsenor_mask_batched", "tsenor_mask", "tsenor_mask_ex_static",
-    "tsenor_mask_ex_profile",
+    "tsenor_mask_ex_profile", "tsenor_last_hip_error",
     "tsenor_status_string", "tsenor_version",
 )
 
@@ -80,7 +80,8 @@ class tsenor_problem(ctypes.Structure):
 class TsenorError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} (status {status})")
+        detail = f", hipError_t {load().tsenor_last_hip_error()}" if status == TSENOR_ERR_HIP else ""
+        super().__init__(f"{where}: {status_string(status)} (status {status}{detail})")
 
 
 _lib = None
@@ -92,6 +93,10 @@ def load() -> ctypes.CDLL:
     if _lib is None:
         if not LIB_PATH.exists():
             raise ImportError(f"{LIB_PATH} is not built; run __graft_entry__.build() first")
+        # PyTorch brings its own copy of the HIP runtime; it has to be in the process before this library is
+        # loaded, so that both use the same one (device pointers and streams of one runtime mean nothing to another)
+        import torch  # noqa: F401
+
         lib = ctypes.CDLL(str(LIB_PATH))
         P = ctypes.POINTER(tsenor_problem)
         lib.tsenor_workspace_bytes.argtypes = [P, ctypes.c_int]
@@ -106,11 +111,12 @@ def load() -> ctypes.CDLL:
         lib.tsenor_mask_ex_static.argtypes = [P, ctypes.c_void_p]
         lib.tsenor_mask_ex_static.restype = ctypes.c_int
         lib.tsenor_mask_ex_profile.argtypes = [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int,
-                                               ctypes.POINTER(ctypes.c_float)]
+                                               ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
         lib.tsenor_mask_ex_profile.restype = ctypes.c_int
         lib.tsenor_status_string.argtypes = [ctypes.c_int]
         lib.tsenor_status_string.restype = ctypes.c_char_p
         lib.tsenor_version.restype = ctypes.c_int
+        lib.tsenor_last_hip_error.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -212,15 +218,17 @@ NUM_STAGES = 4
 STAGE_NAMES = ("reset+absmax", "dykstra+sort", "greedy", "local_search+write")
 
 
-def tsenor_mask_ex_profile(problem, workspace, repeats, stream=None):
-    """Run the path ``repeats`` times, synchronise, return the mean per-stage durations in ms."""
+def tsenor_mask_ex_profile(problem, workspace, repeats, stream=None, want_clock=False):
+    """Run the path ``repeats`` times, synchronise, return the mean per-stage durations in ms (and, if asked for,
+    the shader clock in MHz that the Dykstra kernel's first wave saw over its iteration loop)."""
     ms = (ctypes.c_float * NUM_STAGES)()
+    mhz = ctypes.c_double(0.0)
     rc = load().tsenor_mask_ex_profile(ctypes.byref(problem), ctypes.c_void_p(workspace.data_ptr()),
                                        workspace.numel() * workspace.element_size(), _stream_handle(stream),
-                                       int(repeats), ms)
+                                       int(repeats), ms, ctypes.byref(mhz) if want_clock else None)
     if rc != TSENOR_OK:
         raise TsenorError(rc, "tsenor_mask_ex_profile")
-    return [float(x) for x in ms]
+    return ([float(x) for x in ms], float(mhz.value)) if want_clock else [float(x) for x in ms]
 
 
 def tsenor_mask(W, N, M, tau, iters, mask=None, stream=None):

@@ -266,7 +266,7 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
     xr[rx] = R[0];
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int a = 0; a < TH; ++a) R[a] = xr[a ^ rx];
+    for (int a = 1; a < TH; ++a) R[a] = xr[a ^ rx];  // (register 0 is the owned row: its factor is at hand)
     asm volatile("" ::: "memory");
   } else {
     all_gather_x<T, real, TH>(R);
@@ -301,13 +301,15 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
       C[b] = frozen ? real(1) : C[b];
     }
   }
-  all_gather_y<T, real, TW>(C);
+  // the owner of a column applies its factor and the new scalings (not the factors) are gathered: every lane
+  // would have formed the same products
+#pragma unroll
+  for (int b = 0; b < OWN_C; ++b) V[b] *= C[b];
+  all_gather_y<T, real, TW>(V);
 #pragma unroll
   for (int a = 0; a < TH; ++a)
 #pragma unroll
     for (int b = 0; b < TW; ++b) kap[a][b] *= R[a];
-#pragma unroll
-  for (int b = 0; b < TW; ++b) V[b] *= C[b];
   // lines 5-6 (cap and dual update) are the clamp at the top of the next pass
   return worst;
 }
@@ -357,7 +359,7 @@ __device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW
     xr[rx] = R[0];
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int a = 0; a < TH; ++a) R[a] = xr[a ^ rx];
+    for (int a = 1; a < TH; ++a) R[a] = xr[a ^ rx];
     asm volatile("" ::: "memory");
   } else {
     all_gather_x<T, float, TH>(R);
@@ -378,9 +380,9 @@ __device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW
       C[b] = frozen ? 1.0f : C[b];
     }
   }
-  all_gather_y<T, float, TW>(C);
 #pragma unroll
-  for (int b = 0; b < TW; ++b) V[b] *= C[b];
+  for (int b = 0; b < OWN_C; ++b) V[b] *= C[b];
+  all_gather_y<T, float, TW>(V);
   return worst;
 }
 
@@ -613,6 +615,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
 
     const double Nd = (double)p.N;
     iters_done = p.T;
+    const long long cycles0 = clock64(), ticks0 = wall_clock64();
     // logs of the scalings of the rows and columns this lane owns (the first registers after a
     // reduce-scatter); the other lanes of the lane-row / lane-column hold the same values for theirs
     constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
@@ -758,6 +761,11 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
       }
     }
 
+    if (group == 0 && threadIdx.x == 0) {
+      WsHeader* h = batch.e[which].hdr;
+      h->loop_cycles = (unsigned long long)(clock64() - cycles0);
+      h->loop_ticks = (unsigned long long)(wall_clock64() - ticks0);
+    }
     const int rx2 = fresh(rx), ry2 = fresh(ry);
     double lu[TH], lv[TW];
 #pragma unroll

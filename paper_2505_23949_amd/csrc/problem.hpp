@@ -13,6 +13,9 @@ struct WsHeader {
   double tau_eff;
   unsigned long long stats[4];
   double objective[2];    // sum S*importance of the mask found / of the previous mask
+  // measurement aid: shader-clock cycles and constant-rate timer ticks that the first wave of the Dykstra kernel
+  // spent in its iteration loop (their ratio is the clock the chip held under that load)
+  unsigned long long loop_cycles, loop_ticks;
 };
 static_assert(sizeof(WsHeader) <= 256, "header must fit its slot");
 

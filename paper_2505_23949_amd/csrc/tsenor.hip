@@ -40,6 +40,7 @@ __global__ void init_kernel(Batch batch) {
   hdr->use_prev = 0u;
   hdr->objective[0] = hdr->objective[1] = 0.0;
   hdr->tau_eff = 0.0;
+  hdr->loop_cycles = hdr->loop_ticks = 0ull;
   for (int k = 0; k < 4; ++k) hdr->stats[k] = 0ull;
 }
 
@@ -142,6 +143,15 @@ __global__ void stats_kernel(Batch batch) {
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
+
+// code of the last HIP failure a call of this thread ran into (hipGetLastError() clears the runtime's own copy)
+thread_local int g_last_hip_error = 0;
+inline int hip_status_of_launches() {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return TSENOR_OK;
+  g_last_hip_error = (int)e;
+  return TSENOR_ERR_HIP;
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -313,7 +323,7 @@ int run_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev = n
   if (any_emit) emit_kernel<<<strided_grid(b, true, 2048, false), 256, 0, stream>>>(b);
   if (any_stats) stats_kernel<<<1, 4 * kMaxBatch, 0, stream>>>(b);
   mark(4);
-  return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
+  return hip_status_of_launches();
 }
 
 // N = 0 and N = M need no solve: the mask is constant and the statistics are zero.
@@ -330,7 +340,7 @@ int run_degenerate(const tsenor_problem& p, char* ws, hipStream_t stream, hipEve
   if (p.stats_out) stats_kernel<<<1, 4 * kMaxBatch, 0, stream>>>(b);
   if (p.packed_out || p.pruned_out) emit_kernel<<<strided_grid(b, true, 2048, false), 256, 0, stream>>>(b);
   if (ev) (void)hipEventRecord(ev[4], stream);
-  return hipGetLastError() == hipSuccess ? TSENOR_OK : TSENOR_ERR_HIP;
+  return hip_status_of_launches();
 }
 
 // Everything a call checks before it enqueues anything: every problem on its own, the workspace, and that the
@@ -460,7 +470,7 @@ int tsenor_mask_ex_static(const tsenor_problem* p, tsenor_stream_t stream) {
 }
 
 int tsenor_mask_ex_profile(const tsenor_problem* p, void* workspace, size_t workspace_bytes, tsenor_stream_t stream,
-                           int repeats, float* stage_ms) {
+                           int repeats, float* stage_ms, double* loop_clock_mhz) {
   if (!p || !stage_ms) return TSENOR_ERR_NULL;
   const int rc = check_call(p, 1, workspace, workspace_bytes);
   if (rc != TSENOR_OK) return rc;
@@ -486,6 +496,16 @@ int tsenor_mask_ex_profile(const tsenor_problem* p, void* workspace, size_t work
     }
   for (int k = 0; k < created; ++k) (void)hipEventDestroy(ev[k]);
   delete[] ev;
+  if (loop_clock_mhz) {
+    *loop_clock_mhz = 0.0;
+    WsHeader h;
+    int dev = 0, khz = 0;
+    if (out == TSENOR_OK && !degenerate(*p) &&
+        hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) == hipSuccess && h.loop_ticks > 0 &&
+        hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess)
+      *loop_clock_mhz = (double)h.loop_cycles / (double)h.loop_ticks * (double)khz * 1e-3;
+  }
   return out;
 }
 
@@ -529,6 +549,8 @@ const char* tsenor_status_string(int status) {
   }
   return "unknown status";
 }
+
+int tsenor_last_hip_error(void) { return g_last_hip_error; }
 
 int tsenor_version(void) { return 200; }
 

@@ -95,9 +95,9 @@ def test_validation_errors(lib):
     assert call(good, ws=0x10010) == b.TSENOR_ERR_WORKSPACE          # not 256-byte aligned
     assert call(good, nbytes=need - 1) == b.TSENOR_ERR_WORKSPACE
     stage = (ctypes.c_float * b.NUM_STAGES)()
-    assert lib.tsenor_mask_ex_profile(ctypes.byref(good), ctypes.c_void_p(0x10000), 1 << 40, None, 0, stage) \
+    assert lib.tsenor_mask_ex_profile(ctypes.byref(good), ctypes.c_void_p(0x10000), 1 << 40, None, 0, stage, None) \
         == b.TSENOR_ERR_PARAM
-    assert lib.tsenor_mask_ex_profile(ctypes.byref(good), ctypes.c_void_p(0x10000), 1 << 40, None, 1, None) \
+    assert lib.tsenor_mask_ex_profile(ctypes.byref(good), ctypes.c_void_p(0x10000), 1 << 40, None, 1, None, None) \
         == b.TSENOR_ERR_NULL
     assert lib.tsenor_mask(None, 64, 64, 8, 16, 0.1, 10, ctypes.c_void_p(0x2000), None) == b.TSENOR_ERR_NULL
     assert lib.tsenor_mask(ctypes.c_void_p(0x1000), 64, 60, 8, 16, 0.1, 10, ctypes.c_void_p(0x2000), None) \
