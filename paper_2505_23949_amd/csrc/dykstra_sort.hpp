@@ -36,6 +36,7 @@
 
 #include "lanes.hpp"
 #include "problem.hpp"
+#include "rounding.hpp"
 
 namespace tsenor_dev {
 
@@ -480,11 +481,12 @@ __device__ __forceinline__ void row_chunks(F& f) {
   }
 }
 
-template <int M, bool FAST, bool ADAPT = false>
+template <int M, bool FAST, bool ADAPT = false, bool SMALL = false>
 struct DykstraLaunch {
   // with the early exit the waves of a launch run for very different times; one-wave workgroups let the
-  // dispatcher refill every wave slot as it frees (a four-wave workgroup holds its slots until its slowest wave)
-  static constexpr int kWavesPerGroup = ADAPT ? 1 : 4;
+  // dispatcher refill every wave slot as it frees (a four-wave workgroup holds its slots until its slowest wave).
+  // The small tiles carry the rounding behind the iterations, whose steps synchronise one wave at a time.
+  static constexpr int kWavesPerGroup = (ADAPT || SMALL) ? 1 : 4;
   static constexpr int kThreads = kWavesPerGroup * kWave;
   // waves per SIMD the register budget is set for.  The fp32 loop wants more than two (one wave issues at
   // most every ~5 cycles, an fp32 instruction occupies the SIMD for 2); the kernel needs 158 registers, which
@@ -495,19 +497,22 @@ struct DykstraLaunch {
 
 // ZERO_T: the instantiation for T = 0 (no iterations, keys are K itself).  It is a template parameter
 // rather than a branch because keeping both paths in one kernel costs the iterating path ~40 registers.
+// SMALL: the finer tiling, for launches that cannot fill the chip.  There the whole path stays in this kernel:
+// a block lives in one wave from its tile load to its mask, so the sorted scan order goes to LDS instead of the
+// workspace and Algorithm 2 (greedy selection with M lanes per block, local search, mask write) runs behind the
+// sort; no further kernel follows.
 template <int M, bool FAST, bool ZERO_T = false, bool SMALL = false, bool ADAPT = false>
-__global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (DykstraLaunch<M, FAST, ADAPT>::kWavesPerSimd)) void dykstra_sort_kernel(
+__global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (DykstraLaunch<M, FAST, ADAPT, SMALL>::kWavesPerSimd)) void dykstra_sort_kernel(
     Batch batch) {
   using T = Tiling<M, SMALL>;
   const int which = find_problem(batch, blockIdx.x);
   const DevProblem p = batch.e[which].p;
-  const WsHeader* hdr = batch.e[which].hdr;
   unsigned short* order = batch.e[which].order;
   double* plan_out = batch.e[which].plan_out;
   double* tau_eff_out = batch.e[which].tau_eff_out;
   const unsigned int group = blockIdx.x - batch.first[which];  // workgroup index within the matrix
   constexpr int GX = 1 << T::NX, GY = 1 << T::NY, TH = M / GY, TW = M / GX, LPB = GX * GY, BPW = kWave / LPB,
-                E = TH * TW, SHX = ilog2(TH) - T::NX, WPG = DykstraLaunch<M, FAST, ADAPT>::kWavesPerGroup;
+                E = TH * TW, SHX = ilog2(TH) - T::NX, WPG = DykstraLaunch<M, FAST, ADAPT, SMALL>::kWavesPerGroup;
   const int lane = threadIdx.x & (kWave - 1), wave_in_group = threadIdx.x / kWave;
   const int64_t wave = (int64_t)group * WPG + wave_in_group;
   const int q = lane % LPB, gx = q % GX, gy = q / GX;
@@ -515,7 +520,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
   const bool active = blk < p.nblocks;
   if (!active) blk = p.nblocks - 1;  // idle lanes shadow the last block and write nothing
   const int64_t r0 = (blk / p.bc) * M, c0 = (blk % p.bc) * M;
-  const double tau_eff = tau_eff_of(p, hdr);
+  const double tau_eff = tau_eff_of(batch.e[which]);
   if (tau_eff_out && group == 0 && threadIdx.x == 0) *tau_eff_out = tau_eff;
 
   // register (a, b) of this lane <-> in-kernel coordinates (ri, cj) of the block.  Each phase of the
@@ -828,7 +833,24 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT>::kThreads), (Dykstra
   for (int r = 0; r < E; ++r) asm volatile("" : "+v"(c[r]));
 
   if (active && q == 0 && batch.e[which].iters_done_out) batch.e[which].iters_done_out[blk] = iters_done;
-  if (active) {
+  if constexpr (SMALL) {
+    // Algorithm 2 behind the sort, in the same wave: the scan order of the wave's blocks through LDS
+    static_assert(WPG == 1, "the rounding steps synchronise single-wave workgroups");
+    __shared__ unsigned short scan[BPW][M * M];
+    __shared__ RoundingLds<M, BPW> lds;
+    unsigned short* mine = &scan[lane / LPB][0];
+#pragma unroll
+    for (int r = 0; r < E; ++r)
+      mine[q * E + r] = (unsigned short)((unsigned long long)__double_as_longlong(c[r]) & ((1ull << kIdxBits) - 1));
+    __syncthreads();
+    const int placed = greedy_wide_scan<M, LPB>([&](int pos) { return (unsigned int)mine[pos]; }, p.N, lane, lds);
+    if (batch.e[which].stats_out) {
+      int missing = (active && q == 0) ? p.N * M - placed : 0;
+      for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
+      if (lane == 0 && missing) atomicAdd(&batch.e[which].hdr->stats[0], (unsigned long long)missing);
+    }
+    local_search_and_write<M, LPB>(p, batch.e[which], blk, active, lane, lds);
+  } else if (active) {
     unsigned short* dst = order + blk * (int64_t)(M * M) + q * E;
 #pragma unroll
     for (int r = 0; r < E; ++r)

@@ -3,7 +3,6 @@
 #pragma once
 #include "dykstra_sort.hpp"
 #include "launch.hpp"
-#include "rounding.hpp"
 
 namespace tsenor_dev {
 
@@ -27,18 +26,20 @@ bool launch_block_kernels(Batch& b, const Variant& v, hipStream_t stream, hipEve
   constexpr bool kHasSmall = M <= 32;
   const bool small = kHasSmall && !v.fast && !v.zero_t && v.small;
   if (small) {
+    // the small tiles carry Algorithm 2 behind the iterations: this one kernel is the whole path
     if constexpr (kHasSmall) {
       constexpr int BPWS = kWave >> (Tiling<M, true>::NX + Tiling<M, true>::NY);
-      if (v.adaptive) {
-        using L = DykstraLaunch<M, false, true>;
-        if (!assign_groups(b, (int64_t)BPWS * L::kWavesPerGroup)) return false;
+      using L = DykstraLaunch<M, false, false, true>;
+      static_assert(L::kWavesPerGroup == 1 && DykstraLaunch<M, false, true, true>::kWavesPerGroup == 1, "");
+      if (!assign_groups(b, (int64_t)BPWS)) return false;
+      if (v.adaptive)
         dykstra_sort_kernel<M, false, false, true, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
-      } else {
-        using L = DykstraLaunch<M, false>;
-        if (!assign_groups(b, (int64_t)BPWS * L::kWavesPerGroup)) return false;
+      else
         dykstra_sort_kernel<M, false, false, true><<<b.first[b.count], L::kThreads, 0, stream>>>(b);
-      }
     }
+    if (ev_sorted) (void)hipEventRecord(ev_sorted, stream);
+    if (ev_greedy) (void)hipEventRecord(ev_greedy, stream);
+    return true;
   } else if (v.fast && v.adaptive) {
     using L = DykstraLaunch<M, true, true>;
     if (!assign_groups(b, (int64_t)BPW * L::kWavesPerGroup)) return false;

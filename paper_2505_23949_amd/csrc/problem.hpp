@@ -7,17 +7,21 @@
 
 namespace tsenor_dev {
 
+// Head of a matrix's workspace slice: what the kernels of a call pass to each other besides the scan order.
 struct WsHeader {
-  unsigned int max_bits;  // bit pattern of the largest importance seen (non-negative floats order as uints)
   unsigned int use_prev;  // safeguard verdict: 1 = the caller's previous mask scores higher and is returned
-  double tau_eff;
-  unsigned long long stats[4];
+  unsigned long long stats[4];  // the four rounding counters (accumulated only when the caller asks for them)
   double objective[2];    // sum S*importance of the mask found / of the previous mask
   // measurement aid: shader-clock cycles and constant-rate timer ticks that the first wave of the Dykstra kernel
   // spent in its iteration loop (their ratio is the clock the chip held under that load)
   unsigned long long loop_cycles, loop_ticks;
 };
 static_assert(sizeof(WsHeader) <= 256, "header must fit its slot");
+
+// The importance maximum of a matrix (relative tau) travels as one partial maximum per workgroup of the
+// pre-pass, in the workspace right after the header; the kernel that needs the maximum reduces them itself.
+// No atomic, so nothing has to be cleared before a call.
+constexpr int kMaxAbsmaxPartials = 1024;
 
 struct DevProblem {
   const void* W;
@@ -42,6 +46,8 @@ struct BatchEntry {
   DevProblem p;
   int64_t rows;
   WsHeader* hdr;                // workspace slices of this matrix
+  float* absmax_partial;        // partial maxima of the importance, absmax_count of them (relative tau only)
+  int absmax_count;
   unsigned short* order;
   void* rowmask;
   double* block_objective;      // NULL: no objective asked for
@@ -229,10 +235,14 @@ __device__ __forceinline__ void block_column_importance(const DevProblem& p, int
   }
 }
 
-// multiplier of the importance in the log-kernel K (App. B.1 parameter choice for the relative mode)
-__device__ __forceinline__ double tau_eff_of(const DevProblem& p, const WsHeader* hdr) {
+// multiplier of the importance in the log-kernel K (App. B.1 parameter choice for the relative mode).
+// Called by whole waves: the partial maxima of the pre-pass are reduced across the lanes.
+__device__ __forceinline__ double tau_eff_of(const BatchEntry& e) {
+  const DevProblem& p = e.p;
   if (p.tau_mode == TSENOR_TAU_ABSOLUTE) return p.tau;
-  float mx = __uint_as_float(hdr->max_bits);
+  float mx = 0.0f;
+  for (int k = (int)(threadIdx.x & 63u); k < e.absmax_count; k += 64) mx = fmaxf(mx, e.absmax_partial[k]);
+  for (int s = 1; s < 64; s <<= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
   return mx > 0.0f ? 1.0 / (p.tau * (double)mx) : 0.0;
 }
 

@@ -105,8 +105,10 @@ __global__ __launch_bounds__(kWave) void greedy_kernel(Batch batch) {
     for (int k = 0; k < M; ++k) rowmask[blk * M + k] = rowbits[k][lane];
     missing = need - placed;
   }
-  for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
-  if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
+  if (batch.e[which].stats_out) {
+    for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
+    if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
+  }
 }
 
 // Ablation arm "Simple" (App. B.2.1): row-wise then column-wise N:M rounding of the plan.  In scan order
@@ -153,9 +155,20 @@ __global__ __launch_bounds__(kWave) void simple_round_kernel(Batch batch) {
     for (int k = 0; k < M; ++k) rowmask[blk * M + k] = rowbits[k][lane];
     missing = N * M - placed;
   }
-  for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
-  if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
+  if (batch.e[which].stats_out) {
+    for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
+    if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
+  }
 }
+
+// LDS of the lane-parallel rounding steps for the G blocks a wave holds: the mask as row and column bit masks
+// (rowm[r] bit c == colm[c] bit r == S[r][c]), column counters of the greedy selection, the importance block.
+template <int M, int G>
+struct RoundingLds {
+  block_mask_t<M> rowm[G][M], colm[G][M];
+  unsigned int colcnt[G][M];
+  float imp[G][M * M];
+};
 
 // The same selection with M lanes per block: the block's scan order is taken M entries at a time, one entry
 // per lane, and all M are decided together.  An entry is rejected for certain when the entries before it in
@@ -164,35 +177,29 @@ __global__ __launch_bounds__(kWave) void simple_round_kernel(Batch batch) {
 // for the next round.  The earliest undecided entry of a block always resolves, so the rounds end, and by
 // induction along the scan order every decision equals the sequential one.  Dependent chain: M chunks of a
 // few rounds instead of M*M steps.
-template <int M>
-__global__ __launch_bounds__(kWave) void greedy_wide_kernel(Batch batch) {
+// A block owns LPB >= M consecutive lanes of the wave (LPB a power of two), of which the first M take part;
+// fetch(pos) returns the flat index at scan position pos of this lane's block.  Leaves the mask in lds.rowm and
+// returns the number of entries the lane's block holds.  To be called by whole single-wave workgroups.
+template <int M, int LPB, class Fetch>
+__device__ __forceinline__ int greedy_wide_scan(Fetch&& fetch, int N, int lane, RoundingLds<M, kWave / LPB>& lds) {
   using mask_t = block_mask_t<M>;
-  constexpr int MM = M * M, G = kWave / M;
+  constexpr int MM = M * M;
   constexpr int LOGM = M == 4 ? 2 : M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
-  __shared__ mask_t rowbits[G][M];
-  __shared__ unsigned int colcnt[G][M];
-  const int which = find_problem(batch, blockIdx.x);
-  const unsigned short* order = batch.e[which].order;
-  const int64_t nblocks = batch.e[which].p.nblocks;
-  const int N = batch.e[which].p.N;
-  mask_t* rowmask = static_cast<mask_t*>(batch.e[which].rowmask);
-  WsHeader* hdr = batch.e[which].hdr;
-  const int lane = threadIdx.x, g = lane / M, ql = lane % M;
-  int64_t blk = (int64_t)(blockIdx.x - batch.first[which]) * G + g;
-  const bool active = blk < nblocks;
-  if (!active) blk = nblocks - 1;  // idle groups shadow the last block and write nothing
-  rowbits[g][ql] = 0;
-  colcnt[g][ql] = 0;
+  const int g = lane / LPB, ql = lane % LPB;
+  const bool part = ql < M;
+  if (part) {
+    lds.rowm[g][ql] = 0;
+    lds.colcnt[g][ql] = 0;
+  }
   __syncthreads();
-  const unsigned long long gmask = (M == 64 ? ~0ull : ((1ull << M) - 1)) << (g * M);
+  const unsigned long long gmask = (M == 64 ? ~0ull : ((1ull << M) - 1)) << (g * LPB);
   const unsigned long long earlier = gmask & ((1ull << lane) - 1);  // lanes of this block before this one
-  const unsigned short* src = order + blk * MM + ql;
   const int need = N * M;
   int placed = 0;
-  unsigned int ahead = src[0];
+  unsigned int ahead = part ? fetch(ql) : 0u;
   for (int ch = 0; ch < M; ++ch) {
     const unsigned int idx = ahead & (unsigned)(MM - 1);
-    if (ch + 1 < M) ahead = src[(ch + 1) * M];
+    if (ch + 1 < M && part) ahead = fetch((ch + 1) * M + ql);
     const unsigned int i = idx / M, j = idx % M;
     // lanes of this block whose entry lies in the same row / the same column
     unsigned long long same_row = gmask, same_col = gmask;
@@ -204,8 +211,8 @@ __global__ __launch_bounds__(kWave) void greedy_wide_kernel(Batch batch) {
       same_col &= jb ? cols_b : ~cols_b;
     }
     const unsigned long long before_row = same_row & earlier, before_col = same_col & earlier;
-    const int room_row = N - mask_popc(rowbits[g][i]), room_col = N - (int)colcnt[g][j];
-    bool undecided = room_row > 0 && room_col > 0, take = false;
+    const int room_row = N - mask_popc(lds.rowm[g][i]), room_col = N - (int)lds.colcnt[g][j];
+    bool undecided = part && room_row > 0 && room_col > 0, take = false;
     unsigned long long taken = 0, open = __ballot(undecided);
     while (open) {
       if (undecided) {
@@ -222,17 +229,39 @@ __global__ __launch_bounds__(kWave) void greedy_wide_kernel(Batch batch) {
       open = __ballot(undecided);
     }
     if (take) {
-      atomicOr(&rowbits[g][i], (mask_t)1 << j);
-      atomicAdd(&colcnt[g][j], 1u);
+      atomicOr(&lds.rowm[g][i], (mask_t)1 << j);
+      atomicAdd(&lds.colcnt[g][j], 1u);
     }
     placed += __popcll(taken & gmask);
     __syncthreads();
     if (!__any(placed < need)) break;  // every block of the wave is full
   }
-  if (active) rowmask[blk * M + ql] = rowbits[g][ql];
-  int missing = (active && ql == 0) ? need - placed : 0;
-  for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
-  if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
+  return placed;
+}
+
+template <int M>
+__global__ __launch_bounds__(kWave) void greedy_wide_kernel(Batch batch) {
+  using mask_t = block_mask_t<M>;
+  constexpr int MM = M * M, G = kWave / M;
+  __shared__ RoundingLds<M, G> lds;
+  const int which = find_problem(batch, blockIdx.x);
+  const unsigned short* order = batch.e[which].order;
+  const int64_t nblocks = batch.e[which].p.nblocks;
+  const int N = batch.e[which].p.N;
+  mask_t* rowmask = static_cast<mask_t*>(batch.e[which].rowmask);
+  WsHeader* hdr = batch.e[which].hdr;
+  const int lane = threadIdx.x, g = lane / M, ql = lane % M;
+  int64_t blk = (int64_t)(blockIdx.x - batch.first[which]) * G + g;
+  const bool active = blk < nblocks;
+  if (!active) blk = nblocks - 1;  // idle groups shadow the last block and write nothing
+  const unsigned short* src = order + blk * MM;
+  const int placed = greedy_wide_scan<M, M>([&](int pos) { return (unsigned int)src[pos]; }, N, lane, lds);
+  if (active) rowmask[blk * M + ql] = lds.rowm[g][ql];
+  if (batch.e[which].stats_out) {
+    int missing = (active && ql == 0) ? N * M - placed : 0;
+    for (int s = 1; s < kWave; s <<= 1) missing += __shfl_xor(missing, s, kWave);
+    if (lane == 0 && missing) atomicAdd(&hdr->stats[0], (unsigned long long)missing);
+  }
 }
 
 // Transpose of an M x M bit matrix held as one M-bit row per lane (M consecutive lanes): afterwards the
@@ -289,73 +318,72 @@ __device__ __forceinline__ double group_sum(double v) {
   }
 }
 
-// Algorithm 2 lines 7-13 and the mask write.  M lanes per block (lane r owns row r and column r of the
-// block as bit masks), 64/M blocks per wave, one wave per workgroup.
-template <int M>
-__global__ __launch_bounds__(kWave) void finalize_kernel(Batch batch) {
+// Algorithm 2 lines 7-13 and the mask write for the blocks of one wave.  A block owns LPB >= M consecutive lanes,
+// of which the first M take part: lane r owns row r and column r of the block as bit masks.  On entry lds.rowm
+// holds the mask greedy selection left.  blk: the lane's block (a valid one also for idle lanes, which write
+// nothing: `active`).  To be called by whole single-wave workgroups.
+template <int M, int LPB>
+__device__ __forceinline__ void local_search_and_write(const DevProblem& p, const BatchEntry& e, int64_t blk, bool active,
+                                                       int lane, RoundingLds<M, kWave / LPB>& lds) {
   using mask_t = block_mask_t<M>;
-  constexpr int MM = M * M, G = kWave / M;
-  const int which = find_problem(batch, blockIdx.x);
-  const DevProblem p = batch.e[which].p;
-  const mask_t* rowmask = static_cast<const mask_t*>(batch.e[which].rowmask);
-  uint8_t* mask = batch.e[which].mask;
-  WsHeader* hdr = batch.e[which].hdr;
-  const int wide_store = batch.e[which].wide_store;
-  double* block_objective = batch.e[which].block_objective;
-  const uint8_t* prev_mask = batch.e[which].prev_mask;
-  __shared__ float imp[G][MM];
-  __shared__ mask_t rowm[G][M], colm[G][M];  // rowm[r] bit c == colm[c] bit r == S[r][c]
-  const int lane = threadIdx.x, g = lane / M, ql = lane % M;
-  int64_t blk = (int64_t)(blockIdx.x - batch.first[which]) * G + g;
-  const bool active = blk < p.nblocks;
-  if (!active) blk = p.nblocks - 1;  // idle groups shadow the last block and write nothing
+  constexpr int MM = M * M;
+  uint8_t* mask = e.mask;
+  WsHeader* hdr = e.hdr;
+  const int wide_store = e.wide_store;
+  double* block_objective = e.block_objective;
+  const uint8_t* prev_mask = e.prev_mask;
+  const bool want_stats = e.stats_out != nullptr;
+  const int g = lane / LPB, ql = lane % LPB;
+  const bool part = ql < M;
+  const int qm = ql % M;  // (an index that stays inside the block's LDS rows also for the lanes that only tag along)
   const int64_t r0 = (blk / p.bc) * M, c0 = (blk % p.bc) * M;
   const mask_t one = 1;
 
-  // the mask greedy selection left, and its transpose
+  // the transpose of the mask greedy selection left
   {
-    const mask_t r = rowmask[blk * M + ql];
-    rowm[g][ql] = r;
-    colm[g][ql] = bit_transpose<M>(r, ql);
+    const mask_t r = part ? lds.rowm[g][qm] : (mask_t)0;
+    const mask_t c = bit_transpose<M>(r, qm);
+    if (part) lds.colm[g][qm] = c;
   }
   __syncthreads();
   const auto popc = [](mask_t v) { return mask_popc(v); };
-  const unsigned long long gmask = (M == 64 ? ~0ull : ((1ull << M) - 1)) << (g * M);
-  const bool any_short = __any(popc(rowm[g][ql]) < p.N);
-  if (any_short || block_objective) {
+  const unsigned long long gmask = (M == 64 ? ~0ull : ((1ull << M) - 1)) << (g * LPB);
+  const bool any_short = __any(part && popc(lds.rowm[g][qm]) < p.N);
+  if ((any_short || block_objective) && part) {
     // local search scores on the importance (Eq. 5), staged in LDS: this lane fetches column ql of its
     // block, all M loads in flight at once
     float col[M];
-    block_column_importance<M>(p, r0, c0 + ql, col);
+    block_column_importance<M>(p, r0, c0 + qm, col);
 #pragma unroll
-    for (int k = 0; k < M; ++k) imp[g][k * M + ql] = col[k];
+    for (int k = 0; k < M; ++k) lds.imp[g][k * M + qm] = col[k];
   }
   __syncthreads();
 
   int rounds = 0, nonpos = 0;
   bool open = any_short;  // this block may still take swaps
   while (any_short) {
-    const mask_t Srow = rowm[g][ql];
-    const unsigned long long rb = __ballot(popc(Srow) < p.N) & gmask;
-    const unsigned long long cb = __ballot(popc(colm[g][ql]) < p.N) & gmask;
+    const mask_t Srow = part ? lds.rowm[g][qm] : (mask_t)0;
+    const mask_t Scol = part ? lds.colm[g][qm] : (mask_t)0;
+    const unsigned long long rb = __ballot(part && popc(Srow) < p.N) & gmask;
+    const unsigned long long cb = __ballot(part && popc(Scol) < p.N) & gmask;
     if (rb == 0 || cb == 0 || (p.strict && rounds >= p.L)) open = false;
     if (!__any(open)) break;
     // line 10: the lowest-index row i and column j that are short
-    const int i = open ? (__ffsll((long long)rb) - 1 - g * M) : 0;
-    const int j = open ? (__ffsll((long long)cb) - 1 - g * M) : 0;
+    const int i = open ? (__ffsll((long long)rb) - 1 - g * LPB) : 0;
+    const int j = open ? (__ffsll((long long)cb) - 1 - g * LPB) : 0;
     // line 11 for i' = this lane: columns j' with S[i'][j'] = 1 and S[i][j'] = 0, provided S[i'][j] = 0
-    mask_t cand = Srow & ~rowm[g][i];
-    if (!open || ((colm[g][j] >> ql) & 1)) cand = 0;
-    const double base = (double)imp[g][ql * M + j];
+    mask_t cand = Srow & ~lds.rowm[g][i];
+    if (!open || !part || ((lds.colm[g][j] >> qm) & 1)) cand = 0;
+    const double base = (double)lds.imp[g][qm * M + j];
     SwapBest best = {-std::numeric_limits<double>::infinity(), MM};
     while (__any(cand != 0)) {
       if (cand != 0) {
         const int jp = sizeof(mask_t) == 8 ? __ffsll((long long)cand) - 1 : __ffs((int)cand) - 1;
         cand &= cand - 1;
-        const double sc = ((double)imp[g][i * M + jp] + base) - (double)imp[g][ql * M + jp];
+        const double sc = ((double)lds.imp[g][i * M + jp] + base) - (double)lds.imp[g][qm * M + jp];
         if (best.arg == MM || sc > best.score) {
           best.score = sc;
-          best.arg = ql * M + jp;
+          best.arg = qm * M + jp;
         }
       }
     }
@@ -368,18 +396,18 @@ __global__ __launch_bounds__(kWave) void finalize_kernel(Batch batch) {
     if (apply && ql == 0) {
       // line 13: remove (i', j'), insert (i', j) and (i, j')
       const int ip = best.arg / M, jp = best.arg % M;
-      rowm[g][ip] = (rowm[g][ip] & ~(one << jp)) | (one << j);
-      rowm[g][i] |= one << jp;
-      colm[g][jp] = (colm[g][jp] & ~(one << ip)) | (one << i);
-      colm[g][j] |= one << ip;
+      lds.rowm[g][ip] = (lds.rowm[g][ip] & ~(one << jp)) | (one << j);
+      lds.rowm[g][i] |= one << jp;
+      lds.colm[g][jp] = (lds.colm[g][jp] & ~(one << ip)) | (one << i);
+      lds.colm[g][j] |= one << ip;
       if (!(best.score > 0.0)) ++nonpos;
     }
     __syncthreads();
   }
 
-  if (active) {
-    const mask_t bits = rowm[g][ql];
-    uint8_t* dst = mask + (r0 + ql) * p.cols + c0;
+  if (active && part) {
+    const mask_t bits = lds.rowm[g][qm];
+    uint8_t* dst = mask + (r0 + qm) * p.cols + c0;
     if (wide_store) {
       // 4 mask bytes per 32-bit word: bit k of a nibble goes to byte k
       unsigned int w[M / 4];
@@ -397,14 +425,17 @@ __global__ __launch_bounds__(kWave) void finalize_kernel(Batch batch) {
     } else {
       for (int k = 0; k < M; ++k) dst[k] = (uint8_t)((bits >> k) & 1);
     }
-    if (block_objective) {
-      // sum S * importance of this block for the mask found and for the caller's previous mask: every lane
-      // sums its row left to right, the rows are then added in a fixed butterfly order
-      double mine = 0.0, theirs = 0.0;
+  }
+  if (block_objective) {
+    // sum S * importance of this block for the mask found and for the caller's previous mask: every lane
+    // sums its row left to right, the rows are then added in a fixed butterfly order
+    double mine = 0.0, theirs = 0.0;
+    if (part) {
+      const mask_t bits = lds.rowm[g][qm];
       mask_t prev_bits = 0;
       if (prev_mask) {
         // the previous mask's row as bits: the byte loads are independent of each other
-        const uint8_t* prev = prev_mask + (r0 + ql) * p.cols + c0;
+        const uint8_t* prev = prev_mask + (r0 + qm) * p.cols + c0;
         uint8_t pm[M];
 #pragma unroll
         for (int k = 0; k < M; ++k) pm[k] = prev[k];
@@ -413,24 +444,44 @@ __global__ __launch_bounds__(kWave) void finalize_kernel(Batch batch) {
       }
 #pragma unroll
       for (int k = 0; k < M; ++k) {
-        const double v = (double)imp[g][ql * M + k];
+        const double v = (double)lds.imp[g][qm * M + k];
         mine += ((bits >> k) & 1) ? v : 0.0;
         theirs += ((prev_bits >> k) & 1) ? v : 0.0;
       }
-      mine = group_sum<M>(mine);
-      theirs = group_sum<M>(theirs);
-      if (ql == 0) {
-        block_objective[2 * blk] = mine;
-        block_objective[2 * blk + 1] = theirs;
-      }
     }
-    const int left = p.N - popc(bits);
+    mine = group_sum<M>(mine);
+    theirs = group_sum<M>(theirs);
+    if (active && ql == 0) {
+      block_objective[2 * blk] = mine;
+      block_objective[2 * blk + 1] = theirs;
+    }
+  }
+  if (want_stats && active && part) {
+    const int left = p.N - popc(lds.rowm[g][qm]);
     if (left) atomicAdd(&hdr->stats[3], (unsigned long long)left);
     if (ql == 0) {
       if (nonpos) atomicAdd(&hdr->stats[1], (unsigned long long)nonpos);
       if (!p.strict && rounds > p.L) atomicAdd(&hdr->stats[2], 1ull);
     }
   }
+}
+
+// The stand-alone kernel: M lanes per block, 64/M blocks per wave, one wave per workgroup; the mask greedy
+// selection left comes from the workspace.
+template <int M>
+__global__ __launch_bounds__(kWave) void finalize_kernel(Batch batch) {
+  using mask_t = block_mask_t<M>;
+  constexpr int G = kWave / M;
+  __shared__ RoundingLds<M, G> lds;
+  const int which = find_problem(batch, blockIdx.x);
+  const DevProblem p = batch.e[which].p;
+  const mask_t* rowmask = static_cast<const mask_t*>(batch.e[which].rowmask);
+  const int lane = threadIdx.x, g = lane / M, ql = lane % M;
+  int64_t blk = (int64_t)(blockIdx.x - batch.first[which]) * G + g;
+  const bool active = blk < p.nblocks;
+  if (!active) blk = p.nblocks - 1;  // idle groups shadow the last block and write nothing
+  lds.rowm[g][ql] = rowmask[blk * M + ql];
+  local_search_and_write<M, M>(p, batch.e[which], blk, active, lane, lds);
 }
 
 }  // namespace tsenor_dev

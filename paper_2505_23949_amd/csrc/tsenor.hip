@@ -33,14 +33,10 @@ namespace {
 
 using namespace tsenor_dev;
 
+// clears the rounding counters of every matrix of the batch (launched only when a caller asks for them)
 __global__ void init_kernel(Batch batch) {
   if ((int)threadIdx.x >= batch.count) return;
   WsHeader* hdr = batch.e[threadIdx.x].hdr;
-  hdr->max_bits = 0u;
-  hdr->use_prev = 0u;
-  hdr->objective[0] = hdr->objective[1] = 0.0;
-  hdr->tau_eff = 0.0;
-  hdr->loop_cycles = hdr->loop_ticks = 0ull;
   for (int k = 0; k < 4; ++k) hdr->stats[k] = 0ull;
 }
 
@@ -118,15 +114,14 @@ __global__ __launch_bounds__(256) void absmax_kernel(Batch batch) {
       for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < p.cols; c += (int64_t)gridDim.x * blockDim.x)
         m = fmaxf(m, load_importance(p, r, c));
   }
-  // one atomic per workgroup, and only ~512 workgroups per matrix: atomics on one address take ~12 ns each,
-  // so thousands of them would take longer than the reads
+  // one partial maximum per workgroup (at most ~512 per matrix); whoever needs the maximum reduces them
   __shared__ float wave_max[4];
   for (int s = 1; s < kWave; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, kWave));
   if ((threadIdx.x & (kWave - 1)) == 0) wave_max[threadIdx.x / kWave] = m;
   __syncthreads();
   if (threadIdx.x == 0) {
     m = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
-    atomicMax(&e.hdr->max_bits, __float_as_uint(m));
+    e.absmax_partial[blockIdx.y * gridDim.x + blockIdx.x] = m;
   }
 }
 
@@ -157,7 +152,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-  size_t header, order, accept, objective, total;
+  size_t header, partials, order, accept, objective, total;
 };
 
 // greedy's output: M row bit masks per block, 32-bit words up to M = 32, 64-bit for M = 64
@@ -168,7 +163,8 @@ WsLayout layout_of(const tsenor_problem& p) {
   const size_t elems = (size_t)p.rows * (size_t)p.cols;
   const size_t nblocks = elems / ((size_t)p.M * p.M);
   l.header = 0;
-  l.order = kAlign;
+  l.partials = kAlign;
+  l.order = l.partials + align_up(kMaxAbsmaxPartials * sizeof(float));
   l.accept = l.order + align_up(elems * sizeof(unsigned short));
   l.objective = l.accept + align_up(nblocks * rowmask_bytes_per_block(p.M));
   l.total = l.objective + align_up(nblocks * 2 * sizeof(double));  // per-block objectives (new, previous mask)
@@ -211,10 +207,10 @@ inline Variant variant_of(const tsenor_problem& p) {
   // the tiling is decided from the matrix's own number of blocks, never from what it is fused with: the two
   // tilings differ in the order of the additions inside a row or column sum
   const int64_t nblocks = (p.rows / p.M) * (p.cols / p.M);
-  v.small = p.M <= 32 && !v.fast && !v.zero_t &&
+  v.simple = (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0;
+  v.small = p.M <= 32 && !v.fast && !v.zero_t && !v.simple &&
             ((p.flags & TSENOR_FLAG_TILES_SMALL) != 0 ||
              (!(p.flags & TSENOR_FLAG_TILES_LARGE) && nblocks < small_tiles_below_blocks(p.M)));
-  v.simple = (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0;
   v.adaptive = p.tol > 0.0 && p.iters > 0;
   return v;
 }
@@ -247,6 +243,8 @@ BatchEntry entry_of(const tsenor_problem& p, char* ws) {
   dp.tol = p.tol;
   e.rows = p.rows;
   e.hdr = reinterpret_cast<WsHeader*>(ws + l.header);
+  e.absmax_partial = reinterpret_cast<float*>(ws + l.partials);
+  e.absmax_count = 0;  // set with the grid of the pre-pass
   e.order = reinterpret_cast<unsigned short*>(ws + l.order);
   e.rowmask = ws + l.accept;
   e.block_objective = (p.objective_out || p.prev_mask) ? reinterpret_cast<double*>(ws + l.objective) : nullptr;
@@ -278,12 +276,15 @@ dim3 strided_grid(const Batch& b, bool vec_only, unsigned target, bool for_absma
     int64_t bands = std::min<int64_t>(e.rows, std::max<unsigned>(target / x, 1));
     if (for_absmax && e.absmax_vec) {
       // enough rows per workgroup to give every thread its rows in flight (a narrow matrix shares the
-      // workgroup between rows), and no more workgroups than that: each ends in an atomic on one address
+      // workgroup between rows), and no more workgroups than that: each leaves a partial maximum to be reduced
       const int64_t rows_per_group = (int64_t)(256 / absmax_threads_per_row(per_row, 256)) * kAbsmaxInFlight;
       bands = std::min(bands, (e.rows + rows_per_group - 1) / rows_per_group);
     }
     gy = std::max(gy, (unsigned)bands);
   }
+  // (matrices of different shapes can ask for a wide and for a tall grid: the product stays within the
+  // partial maxima a workspace holds; the kernels stride by the grid they get)
+  if (for_absmax) gy = std::min(gy, (unsigned)kMaxAbsmaxPartials / gx);
   return dim3(gx, gy, (unsigned)b.count);
 }
 
@@ -306,8 +307,12 @@ int run_group(Batch& b, const Variant& v, hipStream_t stream, hipEvent_t* ev = n
     any_stats |= e.stats_out != nullptr;
   }
   mark(0);
-  init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
-  if (any_rel) absmax_kernel<<<strided_grid(b, false, 512, true), 256, 0, stream>>>(b);
+  if (any_stats) init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
+  if (any_rel) {
+    const dim3 grid = strided_grid(b, false, 512, true);
+    for (int k = 0; k < b.count; ++k) b.e[k].absmax_count = (int)(grid.x * grid.y);
+    absmax_kernel<<<grid, 256, 0, stream>>>(b);
+  }
   mark(1);
   hipEvent_t ev_sorted = ev ? ev[2] : nullptr, ev_greedy = ev ? ev[3] : nullptr;
   bool ok = false;
@@ -336,8 +341,10 @@ int run_degenerate(const tsenor_problem& p, char* ws, hipStream_t stream, hipEve
   Batch b = {};
   b.count = 1;
   b.e[0] = entry_of(p, ws);
-  init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
-  if (p.stats_out) stats_kernel<<<1, 4 * kMaxBatch, 0, stream>>>(b);
+  if (p.stats_out) {
+    init_kernel<<<1, kMaxBatch, 0, stream>>>(b);
+    stats_kernel<<<1, 4 * kMaxBatch, 0, stream>>>(b);
+  }
   if (p.packed_out || p.pruned_out) emit_kernel<<<strided_grid(b, true, 2048, false), 256, 0, stream>>>(b);
   if (ev) (void)hipEventRecord(ev[4], stream);
   return hip_status_of_launches();
@@ -500,7 +507,7 @@ int tsenor_mask_ex_profile(const tsenor_problem* p, void* workspace, size_t work
     *loop_clock_mhz = 0.0;
     WsHeader h;
     int dev = 0, khz = 0;
-    if (out == TSENOR_OK && !degenerate(*p) &&
+    if (out == TSENOR_OK && !degenerate(*p) && p->iters > 0 &&
         hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) == hipSuccess && h.loop_ticks > 0 &&
         hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess)

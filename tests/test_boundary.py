@@ -111,9 +111,10 @@ def test_workspace_bytes(lib):
         p = _problem(M=M, N=M // 2, rows=rows, cols=cols, ld=cols)
         need = lib.tsenor_workspace_bytes(ctypes.byref(p), 1)
         blocks = rows * cols // (M * M)
-        # header + one uint16 per weight (greedy scan order) + M row bit masks per block (32- or 64-bit words)
-        # + two doubles per block (objective of the mask found and of the caller's previous mask)
-        lower = 256 + 2 * rows * cols + blocks * M * (8 if M > 32 else 4) + 16 * blocks
+        # header + partial maxima of the pre-pass (1024 floats) + one uint16 per weight (greedy scan order)
+        # + M row bit masks per block (32- or 64-bit words) + two doubles per block (objective of the mask
+        # found and of the caller's previous mask)
+        lower = 256 + 4096 + 2 * rows * cols + blocks * M * (8 if M > 32 else 4) + 16 * blocks
         assert lower <= need <= lower + 768
     arr = (b.tsenor_problem * 2)(_problem(), _problem(M=32, N=16, rows=64, cols=64, ld=64))
     assert lib.tsenor_workspace_bytes(arr, 2) == sum(lib.tsenor_workspace_bytes(ctypes.byref(x), 1) for x in arr)
