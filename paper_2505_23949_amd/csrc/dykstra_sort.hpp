@@ -200,15 +200,30 @@ __device__ __forceinline__ void reduce_scatter_y(real (&v)[TW]) {
     reduce_scatter_y<T, real, TW, S + 1>(v);
   }
 }
-template <class T, class real, int TW, int S = T::NY - 1>
+// (steps S down to LAST; the default is the whole gather)
+template <class T, class real, int TW, int S = T::NY - 1, int LAST = 0>
 __device__ __forceinline__ void all_gather_y(real (&v)[TW]) {
-  if constexpr (S >= 0) {
+  if constexpr (S >= LAST && S >= 0) {
     constexpr int h = TW >> (S + 1);
     if constexpr (h >= 1) {
 #pragma unroll
       for (int b = 0; b < h; ++b) v[b + h] = lane_xor<T::YM[S]>(v[b]);
     }
-    all_gather_y<T, real, TW, S - 1>(v);
+    all_gather_y<T, real, TW, S - 1, LAST>(v);
+  }
+}
+// the lowest step of all_gather_y whose move goes through the LDS crossbar (0: none does, or it is the last one)
+template <class T, int TW, int S = 0>
+constexpr int gather_split_y() {
+  if constexpr (S < T::NY) {
+    constexpr int m = T::YM[S];
+    constexpr bool crossbar = m < 32 && m != 1 && m != 2 && m != 3 && m != 7 && m != 15 && m != 8;
+    if constexpr (crossbar && (TW >> (S + 1)) >= 1)
+      return S;
+    else
+      return gather_split_y<T, TW, S + 1>();
+  } else {
+    return 0;
   }
 }
 // register offset of a lane along y: lane bit YM[s] set <-> register bit log2(TW >> (s+1))
@@ -306,11 +321,19 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
   // would have formed the same products
 #pragma unroll
   for (int b = 0; b < OWN_C; ++b) V[b] *= C[b];
-  all_gather_y<T, real, TW>(V);
+  // the steps of the gather down to the last one that goes through the LDS crossbar are issued before the
+  // rescaling of the tile, the rest after it: the tile's multiplies cover the latency of those moves
+  constexpr int SPLIT = gather_split_y<T, TW>();
+  all_gather_y<T, real, TW, T::NY - 1, SPLIT>(V);
+  if constexpr (SPLIT > 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int a = 0; a < TH; ++a)
 #pragma unroll
     for (int b = 0; b < TW; ++b) kap[a][b] *= R[a];
+  if constexpr (SPLIT > 0) {
+    __builtin_amdgcn_sched_barrier(0);
+    all_gather_y<T, real, TW, SPLIT - 1>(V);
+  }
   // lines 5-6 (cap and dual update) are the clamp at the top of the next pass
   return worst;
 }

@@ -773,7 +773,7 @@ def _sample_block_rows(w, count):
     return picks[:max(count, 3)]
 
 
-def _check_sampled(w, g, mask_host, plan_rows, sample, stats_host=None):
+def _check_sampled(w, g, mask_host, plan_rows, sample, stats_host=None, plan_atol=PLAN_ATOL, min_identical=0.999):
     """mask_host: full mask; plan_rows: dict block-row -> plan rows (or None)."""
     imp = oracle.importance(g["W_f32"], g["col_scale"])
     te = oracle.tau_eff(imp, w.tau, w.tau_mode)          # matrix maximum over the whole matrix
@@ -789,11 +789,11 @@ def _check_sampled(w, g, mask_host, plan_rows, sample, stats_host=None):
         total += same.size
         if plan_rows is not None:
             err = np.abs(plan_rows[br] - np.exp(log_S)).max()
-            assert err <= PLAN_ATOL, f"block-row {br}: plan differs by {err}"
+            assert err <= plan_atol, f"block-row {br}: plan differs by {err}"
         kept_gpu = float((mask_host[rows] * imp_s.astype(np.float64)).sum())
         kept_ref = float((m_ref * imp_s.astype(np.float64)).sum())
         assert abs(kept_gpu - kept_ref) <= 1e-5 * kept_ref
-    assert identical >= 0.999 * total, f"{identical} of {total} sampled blocks identical"
+    assert identical >= min_identical * total, f"{identical} of {total} sampled blocks identical"
     return identical, total
 
 
@@ -961,20 +961,59 @@ def test_fp32_iterations_columns_first_with_column_scale(dev, M, N, dtype):
     assert same.mean() >= 0.999
 
 
-def test_full_size_sampled_parity_fp32_iterations(dev):
+@pytest.mark.parametrize("name,nsample", [("cfg1_2of4_512", 128), ("cfg2_8of16_4096", 12), ("cfg3_16of32_4096x14336", 8),
+                                          ("cfg5_32of64_8192x28672", 3)])
+def test_full_size_sampled_parity_fp32_iterations(dev, name, nsample):
+    # the fp32-iteration mode at full size, in the launch configuration bench.py times: plan within 1e-4 of the
+    # double-precision oracle, >= 99.9 % of the sampled blocks with the oracle's mask, retained importance within
+    # 1e-5 relative per sampled block-row, invariants on the whole mask
     import torch
 
     from paper_2505_23949_amd import binding
 
-    w = synth.CONFIGS["cfg3_16of32_4096x14336"]
+    w = synth.CONFIGS[name]
     g = synth.generate(w)
     W, cs = _to_device(g, w, dev)
+    print(f"[case] fp32 iterations, full size {w.name}", flush=True)
     res = binding.solve(W, w.N, w.M, w.tau, w.iters, col_scale=cs, tau_mode=w.tau_mode,
-                        flags=binding.TSENOR_FLAG_FP32_ITERATIONS)
+                        flags=binding.TSENOR_FLAG_FP32_ITERATIONS, want_plan=True)
     torch.cuda.synchronize()
-    sample = _sample_block_rows(w, 8)
-    identical, total = _check_sampled(w, g, res["mask"].cpu().numpy(), None, sample)
+    sample = _sample_block_rows(w, nsample)
+    plan_rows = {br: res["plan"][br * w.M:(br + 1) * w.M].cpu().numpy() for br in sample}
+    mask_host = res["mask"].cpu().numpy()
+    del res, W
+    torch.cuda.empty_cache()
+    identical, total = _check_sampled(w, g, mask_host, plan_rows, sample, plan_atol=FP32_PLAN_ATOL)
     print(f"  fp32 iterations: {identical} of {total} sampled blocks identical", flush=True)
+
+
+def test_full_layer_fp32_iterations_sampled_parity(dev):
+    # one 8B decoder layer (seven matrices, one batched call) in the fp32-iteration mode, same bars
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    ws = synth.layer_workloads(0)
+    gens, keep, probs, masks = [], [], [], []
+    for w in ws:
+        g = synth.generate(w)
+        W, cs = _to_device(g, w, dev)
+        m = torch.empty(W.shape, dtype=torch.uint8, device=dev)
+        gens.append(g)
+        keep += [W, cs]
+        masks.append(m)
+        probs.append(binding.make_problem(W, w.N, w.M, w.tau, w.iters, mask=m, col_scale=cs, tau_mode=w.tau_mode,
+                                          flags=binding.TSENOR_FLAG_FP32_ITERATIONS))
+    work = torch.empty(binding.tsenor_workspace_bytes(probs), dtype=torch.uint8, device=dev)
+    print("[case] fp32 iterations, one decoder layer batched", flush=True)
+    binding.tsenor_mask_batched(probs, work)
+    torch.cuda.synchronize()
+    same = blocks = 0
+    for w, g, m in zip(ws, gens, masks):
+        identical, total = _check_sampled(w, g, m.cpu().numpy(), None, _sample_block_rows(w, 2), min_identical=0.0)
+        same, blocks = same + identical, blocks + total
+    print(f"  fp32 iterations: {same} of {blocks} sampled blocks identical", flush=True)
+    assert same >= 0.999 * blocks
 
 
 def test_hip_graph_capture_and_replay(dev):
