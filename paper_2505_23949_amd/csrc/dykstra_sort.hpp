@@ -656,6 +656,8 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (
         iters_done = t_done;
       }
     };
+    // FAST: the tile of the fp32 phase, fl32(kap U V)
+    float kap32[FAST ? TH : 1][FAST ? TW : 1];
     {
       double Uown[OWN_R], V[TW];
 #pragma unroll
@@ -694,6 +696,16 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (
           for (int t = 0; t < p.T; ++t) dykstra_iteration<T, T::STORE_E, kLdsGather>(kap, Uown, V, Nd, 1e-300, xr, rx);
         }
       }
+      if constexpr (FAST) {
+        // The first tile of the fp32 phase comes from the double-precision tile while it is still at hand (it
+        // holds kap U; a multiply with V and a conversion per entry, clamped like a rebuilt entry); only a later
+        // rebuild has to read the importance again and go through exp().
+        const double floor32 = 0x1.31c5957a47de2p-120, ceil32 = 0x1.45e3076d61699p+79;  // e^kLogFloor32, e^kLogCeil32
+#pragma unroll
+        for (int a = 0; a < TH; ++a)
+#pragma unroll
+          for (int b = 0; b < TW; ++b) kap32[a][b] = (float)fmin(fmax(kap[a][b] * V[b], floor32), ceil32);
+      }
 #pragma unroll
       for (int a = 0; a < OWN_R; ++a) {
         lu_own[a] = log(Uown[a]);
@@ -710,7 +722,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (
       if (p.T > kWarmIters && !(ADAPT && __all(frozen))) {
         // fp32 phase: kap32 = fl32(kap U V) for the double scalings U V reached so far, and fp32 scalings
         // U32, V32 relative to them.  kap is not kept: a rebuild reloads the importance.
-        float kap32[TH][TW], U32[TH], V32[TW];
+        float U32[TH], V32[TW];
         const float Nf = (float)p.N;
         const float hi = __builtin_ldexpf(1.0f, kDriftBits), lo = __builtin_ldexpf(1.0f, -kDriftBits);
         auto rebuild = [&]() {
@@ -755,7 +767,10 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (
             __builtin_amdgcn_sched_barrier(0);
           }
         };
-        rebuild();
+#pragma unroll
+        for (int a = 0; a < TH; ++a) U32[a] = 1.0f;
+#pragma unroll
+        for (int b = 0; b < TW; ++b) V32[b] = 1.0f;
         bool all_frozen = false;
         for (int t = kWarmIters; t < p.T && !all_frozen;) {
           const int stop = (p.T - t > kChunk) ? t + kChunk : p.T;
