@@ -27,10 +27,9 @@ METRIC = "masked weights/s (Dykstra+rounding), 16:32 @4096x14336; % of roofline"
 HEADLINE = "cfg3_16of32_4096x14336"
 
 # ---- roofline of the dominant kernel (tile load + Algorithm 1 + sort): bound by vector-ALU issue ---------------
-# Useful work: the double-precision vector operations per matrix entry and Dykstra iteration that the
-# linear-domain form of Algorithm 1 needs: capped entry (multiply with clamp), row-sum add, column-sum multiply-add,
-# row rescale of the entry = 4 (a multiply-add counts once: it is one issue slot).  The 64 x 64 kernel cannot keep
-# the capped entries in registers and computes them twice: 5.
+# Useful work: the vector operations per matrix entry and Dykstra iteration that the linear-domain form of
+# Algorithm 1 needs: capped entry (multiply with clamp), row-sum add, column-sum multiply-add, row rescale of the
+# entry = 4 (a multiply-add counts once: it is one issue slot).
 # Peak: one double-precision wave instruction per SIMD every 4 cycles = 16 lanes/clk/SIMD:
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.32 T lane-operations/s (the published 78.6 TFLOP/s counts every
 # operation as a multiply-add, i.e. twice).
@@ -44,8 +43,10 @@ PEAK_F32_PLAIN_TLANEOPS = 57.0
 SURVEY_MODEL_LANE_OPS = 9.0
 
 
-def useful_ops_per_entry_iter(M: int) -> float:
-    return 5.0 if M == 64 else 4.0
+def useful_ops_per_entry_iter(M: int, fp32: bool) -> float:
+    # (the double-precision mode of the 64 x 64 kernel cannot keep the capped entries in registers and computes
+    # them twice)
+    return 5.0 if (M == 64 and not fp32) else 4.0
 
 
 # Vector instructions the compiled default-mode iteration loop issues per wave and iteration, and the matrix
@@ -53,7 +54,9 @@ def useful_ops_per_entry_iter(M: int) -> float:
 # branch; cross-lane ds_swizzle and LDS accesses issue on another pipeline and are not counted).  Keyed by
 # (M, small tiles).
 LOOP_VALU_PER_WAVE_ITER = {
-    (32, False): (169, 2048),
+    (4, False): (116, 1024), (4, True): (38, 256), (8, False): (108, 1024), (8, True): (42, 256),
+    (16, False): (180, 2048), (16, True): (100, 1024), (32, False): (166, 2048), (32, True): (112, 1024),
+    (64, False): (386, 4096),
 }
 # a matrix with fewer blocks than this runs the small-tile instantiation (the library's own choice, mirrored here
 # only to pick the row of the table above)
@@ -227,7 +230,6 @@ def bench_matrix(args, name):
         del ref_in, ref_out
 
     entry_iters = float(weights) * w.iters
-    ops = useful_ops_per_entry_iter(w.M)
     esize = 2 if w.dtype == "bf16" else 4
     work = None
 
@@ -253,6 +255,7 @@ def bench_matrix(args, name):
             out.update({"tol": tol, "mean_iterations": round(float(done.float().mean()), 1),
                         "kernel_ms": round(dyk_ms, 4)})
             return out, mask
+        ops = useful_ops_per_entry_iter(w.M, fp32)
         achieved = ops * entry_iters / (dyk_ms * 1e-3) / 1e12
         peak = PEAK_F32_PLAIN_TLANEOPS if fp32 else PEAK_F64_TLANEOPS
         plain = not (args.rows or args.absolute_tau or args.iters >= 0)
