@@ -243,6 +243,10 @@ def bench_matrix(args, name):
                                     flags=fp32_flag if fp32 else 0, tol=tol, iters_done_out=done)
         if work is None:
             work = torch.empty(binding.tsenor_workspace_bytes([prob]), dtype=torch.uint8, device=dev)
+        # A settling run of `steps` passes comes first: the chip's clock takes some tens of milliseconds of load to
+        # settle after the idle time of the set-up (kernel durations fall by ~10 % over the first 15-20 passes).
+        # Then the warm-up steps, the timed region, and the staged run (events at the stage boundaries).
+        binding.tsenor_mask_ex_profile(prob, work, steps)
         for _ in range(args.warmup):
             binding.tsenor_mask_ex(prob, work)
         # ---- timed region: exactly `steps` calls of tsenor_mask_ex, enqueued back to back on the current stream
@@ -306,20 +310,22 @@ def bench_matrix(args, name):
         diff = (a != b).view(w.rows // w.M, w.M, w.cols // w.M, w.M).any(dim=3).any(dim=1)
         return round(1.0 - float(diff.float().mean()), 6)
 
+    # the optional modes first, the headline mode last
+    other_mode = early_exit = early_exit32 = None
+    if not no_modes:
+        other_mode, mask_o = run_mode(not headline_fp32)
+        early_exit, mask_e = run_mode(False, 1e-5)
+        early_exit32, mask_e32 = run_mode(True, 1e-5)
     if args.tol > 0.0:
         main_mode, mask = run_mode(headline_fp32, args.tol)
         main_mode["roofline"] = None
     else:
         main_mode, mask = run_mode(headline_fp32)
-    other_mode = early_exit = early_exit32 = None
     if not no_modes:
-        other_mode, mask_o = run_mode(not headline_fp32)
         other_mode["blocks_identical_to_headline_mode"] = same_blocks(mask_o, mask)
-        early_exit, mask_e = run_mode(False, 1e-5)
         early_exit["blocks_identical_to_headline_mode"] = same_blocks(mask_e, mask)
-        early_exit32, mask_e = run_mode(True, 1e-5)
-        early_exit32["blocks_identical_to_headline_mode"] = same_blocks(mask_e, mask)
-        del mask_o, mask_e
+        early_exit32["blocks_identical_to_headline_mode"] = same_blocks(mask_e32, mask)
+        del mask_o, mask_e, mask_e32
 
     # the rounding counters of the headline mode, from a call of its own (asking for them adds two tiny kernels)
     stats = torch.zeros(4, dtype=torch.int64, device=dev)

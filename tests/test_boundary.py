@@ -104,6 +104,26 @@ def test_validation_errors(lib):
         == b.TSENOR_ERR_SHAPE
 
 
+def test_limits_checked_before_any_launch(lib):
+    from paper_2505_23949_amd import binding as b
+
+    # fewer than 2^31 blocks of one size in a call: 2^39 weights of 4x4 blocks are 2^35 blocks
+    huge = _problem(M=4, N=2, rows=1 << 20, cols=1 << 19, ld=1 << 19)
+    assert lib.tsenor_workspace_bytes(ctypes.byref(huge), 1) > 0           # a valid problem on its own
+    assert lib.tsenor_mask_ex(ctypes.byref(huge), ctypes.c_void_p(0x10000), 1 << 62, None) == b.TSENOR_ERR_SHAPE
+    # the second problem of a batch is checked before the first one is enqueued
+    arr = (b.tsenor_problem * 2)(_problem(), _problem(N=99))
+    assert lib.tsenor_mask_batched(arr, 2, ctypes.c_void_p(0x10000), 1 << 40, None) == b.TSENOR_ERR_NM
+    # the entry point on the library's fixed scratch refuses what does not fit, before it touches the device
+    big = _problem(M=32, N=16, rows=8192, cols=8192, ld=8192)
+    assert lib.tsenor_workspace_bytes(ctypes.byref(big), 1) > b.STATIC_SCRATCH_BYTES
+    assert lib.tsenor_mask_ex_static(ctypes.byref(big), None) == b.TSENOR_ERR_TOO_LARGE
+    assert lib.tsenor_mask_ex_static(None, None) == b.TSENOR_ERR_NULL
+    assert lib.tsenor_mask_ex_static(ctypes.byref(_problem(M=5)), None) == b.TSENOR_ERR_UNSUPPORTED
+    assert b"TSENOR_STATIC_SCRATCH_BYTES" in lib.tsenor_status_string(b.TSENOR_ERR_TOO_LARGE)
+    assert lib.tsenor_last_hip_error() == 0
+
+
 def test_workspace_bytes(lib):
     from paper_2505_23949_amd import binding as b
 
