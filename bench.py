@@ -63,17 +63,18 @@ LOOP_VALU_PER_WAVE_ITER = {
 SMALL_TILES_BELOW_BLOCKS = {4: 50000, 8: 9000, 16: 9000, 32: 1500, 64: 0}
 
 
-def recorded_traffic(workload: str):
+def recorded_traffic(workload: str, fp32: bool):
     """HBM bytes of the dominant kernel and of the whole pass, per launch, as recorded in the committed
     rocprofv3 summary of this workload (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size;
     not measured in this run)."""
     out = {"kernel": None, "pass": None}
+    tag = "fp32" if fp32 else "fp64"
     path = os.path.join(ROOT, "profiles", f"all_kernels_{workload}.md")
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch dykstra_sort_kernel"):
+            if line.startswith(f"traffic_bytes_per_launch dykstra_sort_kernel {tag}"):
                 out["kernel"] = int(line.split(":")[1])
-            if line.startswith("traffic_bytes_per_pass"):
+            if line.startswith(f"traffic_bytes_per_pass {tag}"):
                 out["pass"] = int(line.split(":")[1])
     except OSError:
         pass
@@ -263,7 +264,7 @@ def bench_matrix(args, name):
         achieved = ops * entry_iters / (dyk_ms * 1e-3) / 1e12
         peak = PEAK_F32_PLAIN_TLANEOPS if fp32 else PEAK_F64_TLANEOPS
         plain = not (args.rows or args.absolute_tau or args.iters >= 0)
-        traffic = recorded_traffic(w.name) if plain and not fp32 else {"kernel": None, "pass": None}
+        traffic = recorded_traffic(w.name, fp32) if plain else {"kernel": None, "pass": None}
         roofline = {
             "bound": "alu", "kernel": f"dykstra_sort_kernel<{w.M}{', fp32 iterations' if fp32 else ''}>",
             "achieved": round(achieved, 3), "peak": round(peak, 3), "unit": "T lane-ops/s",

@@ -85,7 +85,9 @@ enum {
    * adds issue 1.5-1.8 times as fast as double-precision ones on MI355X).  The potentials then carry ~1e-6 of rounding noise: the plan agrees with a
    * double-precision evaluation to ~1e-5 instead of ~1e-13, and the greedy order - hence the mask - can
    * differ from it in a block where two plan entries are closer than that (none in 8192 blocks of the
-   * 16:32 test workload).  Sort keys, swap scores and all results stay in double.  Off by default. */
+   * 16:32 test workload).  Sort keys, swap scores and all results stay in double.  Off by default.  A matrix that
+   * runs on the small tiles (below) iterates in double whatever this flag says: such a launch is bound by latency,
+   * not by instruction issue, and single precision would buy nothing. */
   TSENOR_FLAG_FP32_ITERATIONS = 1u << 2,
   /* Which kernel runs the greedy selection (Algorithm 2 lines 1-6).  Both give the same mask.  One takes
    * one lane per block (fewest instructions: best when tens of thousands of blocks fill the chip), the other
@@ -96,10 +98,11 @@ enum {
   TSENOR_FLAG_GREEDY_M_LANES = 1u << 4,
   /* How the Dykstra kernel spreads a block over lanes.  Same arithmetic, same results up to the order of
    * the additions inside a row or column sum (~1e-15).  LARGE tiles: 32 entries per lane (16 for M <= 8),
-   * fewest instructions per entry: best for full matrices.  SMALL tiles (M <= 32, double-precision
-   * iterations with iters > 0; ignored otherwise): 16 entries per lane (4 for M <= 8),
+   * fewest instructions per entry: best for full matrices.  SMALL tiles (M <= 32, iters > 0, not with
+   * TSENOR_FLAG_SIMPLE_ROUNDING; ignored otherwise): 16 entries per lane (4 for M <= 8),
    * more lanes per block, a shorter dependent chain per iteration: best while the launch cannot fill the
-   * chip anyway.  Default: chosen by the number of blocks in the launch.  Setting both is an error. */
+   * chip anyway; on them the whole path, Algorithm 2 included, runs in one kernel (the TSENOR_FLAG_GREEDY_* choice
+   * does not apply).  Default: chosen by the number of blocks of the matrix.  Setting both is an error. */
   TSENOR_FLAG_TILES_LARGE = 1u << 5,
   TSENOR_FLAG_TILES_SMALL = 1u << 6,
   /* Ablation arm "Simple" of App. B.2.1 in place of Algorithm 2: per block, keep the N largest plan entries

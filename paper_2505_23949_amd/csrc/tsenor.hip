@@ -201,16 +201,17 @@ inline bool degenerate(const tsenor_problem& p) { return p.N == 0 || p.N == p.M;
 inline Variant variant_of(const tsenor_problem& p) {
   Variant v;
   v.M = p.M;
-  v.fast = p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0;
   v.zero_t = p.iters == 0;
   v.greedy = p.flags & (uint32_t)(TSENOR_FLAG_GREEDY_ONE_LANE | TSENOR_FLAG_GREEDY_M_LANES);
+  v.simple = (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0;
   // the tiling is decided from the matrix's own number of blocks, never from what it is fused with: the two
   // tilings differ in the order of the additions inside a row or column sum
   const int64_t nblocks = (p.rows / p.M) * (p.cols / p.M);
-  v.simple = (p.flags & TSENOR_FLAG_SIMPLE_ROUNDING) != 0;
-  v.small = p.M <= 32 && !v.fast && !v.zero_t && !v.simple &&
+  v.small = p.M <= 32 && !v.zero_t && !v.simple &&
             ((p.flags & TSENOR_FLAG_TILES_SMALL) != 0 ||
              (!(p.flags & TSENOR_FLAG_TILES_LARGE) && nblocks < small_tiles_below_blocks(p.M)));
+  // the small tiles (launches that cannot fill the chip: bound by latency, not by issue) iterate in double only
+  v.fast = p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0 && !v.small;
   v.adaptive = p.tol > 0.0 && p.iters > 0;
   return v;
 }
