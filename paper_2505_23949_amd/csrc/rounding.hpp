@@ -167,7 +167,9 @@ template <int M, int G>
 struct RoundingLds {
   block_mask_t<M> rowm[G][M], colm[G][M];
   unsigned int colcnt[G][M];
-  float imp[G][M * M];
+  // (rows padded by one float: lane r reads row r, and with a row length of M every lane would hit the same bank)
+  static constexpr int kImpLd = M + 1;
+  float imp[G][M * kImpLd];
 };
 
 // The same selection with M lanes per block: the block's scan order is taken M entries at a time, one entry
@@ -326,7 +328,7 @@ template <int M, int LPB>
 __device__ __forceinline__ void local_search_and_write(const DevProblem& p, const BatchEntry& e, int64_t blk, bool active,
                                                        int lane, RoundingLds<M, kWave / LPB>& lds) {
   using mask_t = block_mask_t<M>;
-  constexpr int MM = M * M;
+  constexpr int MM = M * M, LD = RoundingLds<M, kWave / LPB>::kImpLd;
   uint8_t* mask = e.mask;
   WsHeader* hdr = e.hdr;
   const int wide_store = e.wide_store;
@@ -355,7 +357,7 @@ __device__ __forceinline__ void local_search_and_write(const DevProblem& p, cons
     float col[M];
     block_column_importance<M>(p, r0, c0 + qm, col);
 #pragma unroll
-    for (int k = 0; k < M; ++k) lds.imp[g][k * M + qm] = col[k];
+    for (int k = 0; k < M; ++k) lds.imp[g][k * LD + qm] = col[k];
   }
   __syncthreads();
 
@@ -374,13 +376,13 @@ __device__ __forceinline__ void local_search_and_write(const DevProblem& p, cons
     // line 11 for i' = this lane: columns j' with S[i'][j'] = 1 and S[i][j'] = 0, provided S[i'][j] = 0
     mask_t cand = Srow & ~lds.rowm[g][i];
     if (!open || !part || ((lds.colm[g][j] >> qm) & 1)) cand = 0;
-    const double base = (double)lds.imp[g][qm * M + j];
+    const double base = (double)lds.imp[g][qm * LD + j];
     SwapBest best = {-std::numeric_limits<double>::infinity(), MM};
     while (__any(cand != 0)) {
       if (cand != 0) {
         const int jp = sizeof(mask_t) == 8 ? __ffsll((long long)cand) - 1 : __ffs((int)cand) - 1;
         cand &= cand - 1;
-        const double sc = ((double)lds.imp[g][i * M + jp] + base) - (double)lds.imp[g][qm * M + jp];
+        const double sc = ((double)lds.imp[g][i * LD + jp] + base) - (double)lds.imp[g][qm * LD + jp];
         if (best.arg == MM || sc > best.score) {
           best.score = sc;
           best.arg = qm * M + jp;
@@ -444,7 +446,7 @@ __device__ __forceinline__ void local_search_and_write(const DevProblem& p, cons
       }
 #pragma unroll
       for (int k = 0; k < M; ++k) {
-        const double v = (double)lds.imp[g][qm * M + k];
+        const double v = (double)lds.imp[g][qm * LD + k];
         mine += ((bits >> k) & 1) ? v : 0.0;
         theirs += ((prev_bits >> k) & 1) ? v : 0.0;
       }
