@@ -63,6 +63,9 @@ enum { TSENOR_F32 = 0, TSENOR_BF16 = 1 }; /* storage type of W; bf16 is widened 
  *   REL_MATRIX_MAX  K_ij = imp_ij / (tau * max_ij imp_ij): the entropy weight 1/tau_eff of Eq. 4 is
  *                   tau times the largest importance of this matrix (the parameter choice of
  *                   App. B.1, "0.005 max|W|", read so that it is consistent with Eq. 4).
+ * In REL_MATRIX_MAX mode a call starts with a pass over W that finds the maximum; a caller that knows it can
+ * pass ABSOLUTE with tau = 1 / (coefficient * maximum) instead and save that kernel (a small launch is then a
+ * single kernel).
  * In REL_MATRIX_MAX mode tau must be >= 1/690 (K <= 690 natural-log units), else TSENOR_ERR_PARAM.
  * In ABSOLUTE mode K is not bounded by the call; the supported range is a spread of K of at most ~700
  * inside any one row of a block (column, with TSENOR_FLAG_COLS_FIRST): entries further below their row's
