@@ -9,7 +9,7 @@ Inputs are synthetic (seeded) and already resident in HBM when the timed region 
 Prints ONE JSON line: whole-job throughput in masked weights/s over the timed tsenor_mask_ex calls, the roofline
 of the dominant kernel (its duration from HIP events at the stage boundaries of a second, equally long run of
 the same calls), and the CPU oracle timed on a bounded sample.  `--workload all` measures every configuration,
-writes one such line per configuration into gpurun_out/ and prints the headline one.
+writes one such line per configuration into --out-dir and prints the headline one.
 """
 from __future__ import annotations
 
@@ -38,9 +38,9 @@ PEAK_F64_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # measured on this chip for plain v_mul_f32 / v_add_f32 / v_fma_f32 is 48-57 T lane-operations/s
 # (profiles/issue_rates_mi355x.md); the upper end is taken as the peak.
 PEAK_F32_PLAIN_TLANEOPS = 57.0
-# The survey's model of the method (5 full-rate vector operations + 1 quarter-rate exponential per entry and
+# A coarser model of the method (5 full-rate vector operations + 1 quarter-rate exponential per entry and
 # iteration = 9 lane-cycles), kept only as a comparison figure: this kernel has no transcendental in its loop.
-SURVEY_MODEL_LANE_OPS = 9.0
+NINE_OP_MODEL_LANE_OPS = 9.0
 
 
 def useful_ops_per_entry_iter(M: int, fp32: bool) -> float:
@@ -283,7 +283,7 @@ def bench_matrix(args, name):
             "stage_ms": {n: round(v, 4) for n, v in zip(binding.STAGE_NAMES, stage_ms)},
             "staged_ms_per_step": round(sum(stage_ms), 4),
             "shader_clock_mhz_in_loop": round(clock_mhz, 1),
-            "vs_survey_9op_model": round(SURVEY_MODEL_LANE_OPS * entry_iters / (dyk_ms * 1e-3) / 1e12 / peak, 4),
+            "vs_9op_model": round(NINE_OP_MODEL_LANE_OPS * entry_iters / (dyk_ms * 1e-3) / 1e12 / peak, 4),
             "algorithmic_bytes_per_pass": weights * (esize + 1) + (0 if cs is None else 4 * w.cols),
             "pass_traffic_recorded_in_profiles": traffic["pass"],
         }
@@ -415,7 +415,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=HEADLINE,
                     help="a configuration name, cfg4_layer, slab_loop, or all (one line per configuration into "
-                         "gpurun_out/, the headline line on stdout)")
+                         "--out-dir, the headline line on stdout)")
+    ap.add_argument("--out-dir", default=os.path.join(ROOT, "gpurun_out"),
+                    help="where --workload all writes bench_<name>.json")
     ap.add_argument("--rows", type=int, default=0, help="override rows (debug)")
     ap.add_argument("--cols", type=int, default=0, help="override cols (debug)")
     ap.add_argument("--iters", type=int, default=-1, help="override the iteration count T (debug)")
@@ -440,8 +442,8 @@ def main() -> int:
                          "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (blocks are independent; see DESIGN.md for how the "
-              "path would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (blocks are independent, so the path would shard by "
+              "block range with no communication); run with --gpus 1", file=sys.stderr)
         return 2
 
     from paper_2505_23949_amd import binding, synth
@@ -456,12 +458,12 @@ def main() -> int:
         return bench_matrix(args, name)
 
     if args.workload == "all":
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        os.makedirs(args.out_dir, exist_ok=True)
         headline = None
         for name in [n for n in synth.CONFIGS if n != HEADLINE] + ["cfg4_layer", "slab_loop", HEADLINE]:
             print(f"bench.py: {name}", file=sys.stderr, flush=True)
             out = run(name)
-            with open(os.path.join(ROOT, "gpurun_out", f"bench_{name}.json"), "w") as fh:
+            with open(os.path.join(args.out_dir, f"bench_{name}.json"), "w") as fh:
                 fh.write(json.dumps(out) + "\n")
             headline = out
         print(json.dumps(headline), flush=True)
