@@ -27,7 +27,7 @@
  *     prev_mask and iters_done_out are TSENOR_ERR_UNSUPPORTED for them: there is
  *     nothing to compare or count).
  *   - The arithmetic of the Dykstra iterations, the sort keys and the swap scores
- *     is IEEE double precision on the device (iterations after the eighth in single
+ *     is IEEE double precision on the device (iterations after the fourth in single
  *     precision with TSENOR_FLAG_FP32_ITERATIONS).
  */
 #ifndef TSENOR_H
@@ -84,7 +84,7 @@ enum {
   /* project onto the column-sum set before the row-sum set (the order of the listing in App. A.2);
    * default is rows first as in Algorithm 1 */
   TSENOR_FLAG_COLS_FIRST = 1u << 1,
-  /* Run the Dykstra iterations after the eighth in single precision (single-precision multiplies and
+  /* Run the Dykstra iterations after the fourth in single precision (single-precision multiplies and
    * adds issue 1.5-1.8 times as fast as double-precision ones on MI355X).  The potentials then carry ~1e-6 of rounding noise: the plan agrees with a
    * double-precision evaluation to ~1e-5 instead of ~1e-13, and the greedy order - hence the mask - can
    * differ from it in a block where two plan entries are closer than that (none in 8192 blocks of the
@@ -159,7 +159,7 @@ typedef struct tsenor_problem {
                              > 0: `iters` is a bound ("maximum iterations"): a block stops after a
                              TSENOR_ADAPTIVE_CHECK_EVERY-th iteration in which every row and column scaling factor
                              (N / row sum, N / column sum) was within tol of 1.  Changes the result by O(tol).
-                             With TSENOR_FLAG_FP32_ITERATIONS the factors after the eighth iteration are
+                             With TSENOR_FLAG_FP32_ITERATIONS the factors after the fourth iteration are
                              single-precision numbers: a tol below ~1e-6 is then never met */
   int32_t* iters_done_out; /* device, optional, one int per block (block-row major): iterations that block ran */
 } tsenor_problem;

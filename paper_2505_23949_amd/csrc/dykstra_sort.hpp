@@ -42,7 +42,7 @@ namespace tsenor_dev {
 
 constexpr double kMinLogKernel = -700.0;  // exp(-700) is still a normal double
 constexpr int kIdxBits = 12;              // flat index within a block: up to 64*64 entries
-constexpr int kWarmIters = 8;             // FAST: iterations done in double before switching to fp32
+constexpr int kWarmIters = 4;             // FAST: iterations done in double before switching to fp32
 constexpr int kRowChunks64 = 2;           // M = 64: the 8 x 8 tile is loaded in this many pieces (loads in flight cost registers)
 constexpr int kChunk = 8;                 // FAST: iterations between range checks of the fp32 scalings
 constexpr int kDriftBits = 40;            // FAST: fold the fp32 scalings back beyond 2^+-kDriftBits
@@ -121,18 +121,15 @@ constexpr int owned(int count, int steps) { return (count >> steps) > 0 ? (count
 // rows than the lane-row has lanes, gx shifted up otherwise
 constexpr int shift_lane(int x, int sh) { return sh >= 0 ? x << sh : x >> -sh; }
 
-// 1/d from the hardware estimate x0 (~24 bits for double).  With e = 1 - d x0, 1/d = x0 (1 + e + e^2 + ...):
-// the terms up to e^2 leave an error of e^3 ~ 2^-72, in three fused operations.  One Newton step for float.
+// 1/d from the hardware estimate x0.  A scaling factor is applied once and the sums of the next iteration see
+// its error, so errors of the reciprocal do not accumulate over the iterations, while every refinement step sits
+// in the dependent chain of each of them.  Double: x0 has ~24 bits; with e = 1 - d x0 one Newton step
+// x0 (1 + e) leaves e^2 ~ 2^-48, two fused operations.  Float: the estimate itself (1 ulp).
 __device__ __forceinline__ double fast_rcp(double d) {
   const double x = __builtin_amdgcn_rcp(d);
-  const double e = fma(-d, x, 1.0);
-  return fma(fma(e, e, e), x, x);
+  return fma(fma(-d, x, 1.0), x, x);
 }
-__device__ __forceinline__ float fast_rcp(float d) {
-  float x = __builtin_amdgcn_rcpf(d);
-  x = fmaf(fmaf(-d, x, 1.0f), x, x);
-  return x;
-}
+__device__ __forceinline__ float fast_rcp(float d) { return __builtin_amdgcn_rcpf(d); }
 __device__ __forceinline__ double clamp01(double x) { return fmin(fmax(x, 0.0), 1.0); }
 __device__ __forceinline__ float clamp01(float x) { return fminf(fmaxf(x, 0.0f), 1.0f); }
 __device__ __forceinline__ double vmax(double a, double b) { return fmax(a, b); }
@@ -355,7 +352,7 @@ __device__ __forceinline__ float mul_clamp01(float x, float y) {
 // ADAPT as in dykstra_iteration.
 template <class T, bool LDS_GATHER = false, bool ADAPT = false, int TH, int TW>
 __device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW], float (&U)[TH], float (&V)[TW],
-                                                       float Nf, float* xr = nullptr, int rx = 0,
+                                                       float Nf, float2* xr = nullptr, int rx = 0,
                                                        bool frozen = false) {
   constexpr int OWN_R = owned(TH, T::NX), OWN_C = owned(TW, T::NY);
   float worst = 0;
@@ -378,23 +375,29 @@ __device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW
     }
   }
   if constexpr (LDS_GATHER) {
-    // the factor of the owned row through LDS (see dykstra_iteration)
+    // the owner of a row updates its scaling and leaves factor and scaling in LDS; the other lanes of the
+    // lane-row pick both up in one 8-byte read per row instead of multiplying each scaling themselves
     static_assert(OWN_R == 1, "one owned row per lane");
-    xr[rx] = R[0];
+    U[0] *= R[0];
+    xr[rx] = make_float2(R[0], U[0]);
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int a = 1; a < TH; ++a) R[a] = xr[a ^ rx];
+    for (int a = 1; a < TH; ++a) {
+      const float2 ru = xr[a ^ rx];
+      R[a] = ru.x;
+      U[a] = ru.y;
+    }
     asm volatile("" ::: "memory");
   } else {
     all_gather_x<T, float, TH>(R);
+#pragma unroll
+    for (int a = 0; a < TH; ++a) U[a] *= R[a];
   }
 #pragma unroll
   for (int b = 0; b < TW; ++b) {
 #pragma unroll
     for (int a = 0; a < TH; ++a) C[b] = a == 0 ? e[a][b] * R[a] : fmaf(e[a][b], R[a], C[b]);
   }
-#pragma unroll
-  for (int a = 0; a < TH; ++a) U[a] *= R[a];
   reduce_scatter_y<T, float, TW>(C);
 #pragma unroll
   for (int b = 0; b < OWN_C; ++b) {
@@ -775,8 +778,8 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (
         for (int t = kWarmIters; t < p.T && !all_frozen;) {
           const int stop = (p.T - t > kChunk) ? t + kChunk : p.T;
           constexpr bool kLdsGather32 = M == 32 || M == 64;
-          __shared__ float xrows32[kLdsGather32 ? WPG : 1][kLdsGather32 ? kWave / 8 : 1][8];
-          float* xr = kLdsGather32 ? &xrows32[wave_in_group][lane / 8][0] : nullptr;
+          __shared__ float2 xrows32[kLdsGather32 ? WPG : 1][kLdsGather32 ? kWave / 8 : 1][8];
+          float2* xr = kLdsGather32 ? &xrows32[wave_in_group][lane / 8][0] : nullptr;
           if constexpr (ADAPT) {
             for (; t < stop && !all_frozen; ++t) {
               const float worst =
