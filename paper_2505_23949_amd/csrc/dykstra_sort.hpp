@@ -275,11 +275,11 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
     // the owner of a row leaves its scaling in LDS and every lane of the lane-row picks up all TH of them:
     // LDS instructions instead of vector-ALU moves.  The lanes of a wave run in lock step, so the exchange
     // needs no barrier, only that the compiler keeps the accesses where they are.
-    static_assert(OWN_R == 1, "one owned row per lane");
-    xr[rx] = R[0];
+#pragma unroll
+    for (int a = 0; a < OWN_R; ++a) xr[a ^ rx] = R[a];
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int a = 1; a < TH; ++a) R[a] = xr[a ^ rx];  // (register 0 is the owned row: its factor is at hand)
+    for (int a = OWN_R; a < TH; ++a) R[a] = xr[a ^ rx];  // (the owned rows' factors are at hand)
     asm volatile("" ::: "memory");
   } else {
     all_gather_x<T, real, TH>(R);
@@ -377,12 +377,14 @@ __device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW
   if constexpr (LDS_GATHER) {
     // the owner of a row updates its scaling and leaves factor and scaling in LDS; the other lanes of the
     // lane-row pick both up in one 8-byte read per row instead of multiplying each scaling themselves
-    static_assert(OWN_R == 1, "one owned row per lane");
-    U[0] *= R[0];
-    xr[rx] = make_float2(R[0], U[0]);
+#pragma unroll
+    for (int a = 0; a < OWN_R; ++a) {
+      U[a] *= R[a];
+      xr[a ^ rx] = make_float2(R[a], U[a]);
+    }
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int a = 1; a < TH; ++a) {
+    for (int a = OWN_R; a < TH; ++a) {
       const float2 ru = xr[a ^ rx];
       R[a] = ru.x;
       U[a] = ru.y;
@@ -680,9 +682,9 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (
         // In the 32- and 64-wide kernels the row scalings of an iteration are gathered through LDS (measured
         // ~1 % faster than DPP moves; doing the same for the column scalings as well exposed a second LDS round
         // trip and gained nothing): lane-row r of the wave keeps its 8 row scalings at xrows[wave][r][0..8)
-        constexpr bool kLdsGather = (M == 32 || M == 64) && !SMALL;
-        __shared__ double xrows[kLdsGather ? WPG : 1][kLdsGather ? kWave / 8 : 1][8];
-        double* xr = kLdsGather ? &xrows[wave_in_group][lane / 8][0] : nullptr;
+        constexpr bool kLdsGather = M >= 32 && !SMALL;
+        __shared__ double xrows[kLdsGather ? WPG : 1][kLdsGather ? kWave >> T::NX : 1][TH];
+        double* xr = kLdsGather ? &xrows[wave_in_group][lane >> T::NX][0] : nullptr;
         if constexpr (ADAPT) {
           // iteration count as a bound: every TSENOR_ADAPTIVE_CHECK_EVERY-th iteration the largest |factor - 1|
           // of the block is compared with the tolerance; a block that passes is frozen, the wave leaves when
@@ -777,9 +779,11 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (
         bool all_frozen = false;
         for (int t = kWarmIters; t < p.T && !all_frozen;) {
           const int stop = (p.T - t > kChunk) ? t + kChunk : p.T;
-          constexpr bool kLdsGather32 = M == 32 || M == 64;
-          __shared__ float2 xrows32[kLdsGather32 ? WPG : 1][kLdsGather32 ? kWave / 8 : 1][8];
-          float2* xr = kLdsGather32 ? &xrows32[wave_in_group][lane / 8][0] : nullptr;
+          // (in fp32 the exchange also carries the updated scalings, which pays wherever a block spans lanes:
+          // -6 % for M = 8, -10 % for M = 16; in double the 16-wide kernel is 1.5 % faster with DPP moves)
+          constexpr bool kLdsGather32 = M >= 8;
+          __shared__ float2 xrows32[kLdsGather32 ? WPG : 1][kLdsGather32 ? kWave >> T::NX : 1][TH];
+          float2* xr = kLdsGather32 ? &xrows32[wave_in_group][lane >> T::NX][0] : nullptr;
           if constexpr (ADAPT) {
             for (; t < stop && !all_frozen; ++t) {
               const float worst =
