@@ -49,6 +49,7 @@ constexpr int kDriftBits = 40;            // FAST: fold the fp32 scalings back b
 constexpr double kLogFloor32 = -83.0;     // FAST: rebuilt entries are kept within [e^-83, e^55] ~ [2^-120, 2^80]
 constexpr double kLogCeil32 = 55.0;
 
+
 constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 
 // Per-M tiling.  XM[s] / YM[s]: lane masks of the exchange steps along a lane-row / lane-column.
@@ -232,6 +233,18 @@ __device__ __forceinline__ int reg_xor_y(int q) {
     return 0;
 }
 
+// An iteration alternates between two kinds of code: long runs of independent per-entry arithmetic, and the
+// short dependent chains between them (exchange steps of a reduction, reciprocal, gather of the result) on
+// which the next run waits.  A wave raises its priority for the chains, so that the SIMD issues their few
+// instructions ahead of another wave's long run instead of behind it: with equal priorities the waves of a
+// SIMD fell into step and stalled together (measured: 11-16 % of the fp32 loop, 1-2 % of the double one).
+__device__ __forceinline__ void chain_phase(bool on) {
+  if (on)
+    __builtin_amdgcn_s_setprio(1);
+  else
+    __builtin_amdgcn_s_setprio(0);
+}
+
 // One iteration of Algorithm 1 (lines 3-6) on the register tile of this lane.  The row scalings are folded
 // into the tile as they are found (kap holds kappa_ij U_i), so an entry costs one multiply with its column
 // scaling, and only the scalings of the rows this lane owns are kept as numbers (Uown, for the potentials at
@@ -261,6 +274,7 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
     }
     R[a] = s;
   }
+  chain_phase(true);
   reduce_scatter_x<T, real, TH>(R);
 #pragma unroll
   for (int a = 0; a < OWN_R; ++a) {
@@ -284,6 +298,7 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
   } else {
     all_gather_x<T, real, TH>(R);
   }
+  chain_phase(false);
   // projection onto C2 (line 4)
   real Vc[TW];
 #pragma unroll
@@ -305,6 +320,7 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
     }
     C[b] = s;
   }
+  chain_phase(true);
   reduce_scatter_y<T, real, TW>(C);
 #pragma unroll
   for (int b = 0; b < OWN_C; ++b) {
@@ -322,6 +338,7 @@ __device__ __forceinline__ real dykstra_iteration(real (&kap)[TH][TW], real (&Uo
   // rescaling of the tile, the rest after it: the tile's multiplies cover the latency of those moves
   constexpr int SPLIT = gather_split_y<T, TW>();
   all_gather_y<T, real, TW, T::NY - 1, SPLIT>(V);
+  chain_phase(false);
   if constexpr (SPLIT > 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int a = 0; a < TH; ++a)
@@ -365,6 +382,7 @@ __device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW
       R[a] = b == 0 ? e[a][b] : R[a] + e[a][b];
     }
   }
+  chain_phase(true);
   reduce_scatter_x<T, float, TH>(R);
 #pragma unroll
   for (int a = 0; a < OWN_R; ++a) {
@@ -395,11 +413,13 @@ __device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW
 #pragma unroll
     for (int a = 0; a < TH; ++a) U[a] *= R[a];
   }
+  chain_phase(false);
 #pragma unroll
   for (int b = 0; b < TW; ++b) {
 #pragma unroll
     for (int a = 0; a < TH; ++a) C[b] = a == 0 ? e[a][b] * R[a] : fmaf(e[a][b], R[a], C[b]);
   }
+  chain_phase(true);
   reduce_scatter_y<T, float, TW>(C);
 #pragma unroll
   for (int b = 0; b < OWN_C; ++b) {
@@ -412,6 +432,7 @@ __device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW
 #pragma unroll
   for (int b = 0; b < OWN_C; ++b) V[b] *= C[b];
   all_gather_y<T, float, TW>(V);
+  chain_phase(false);
   return worst;
 }
 
@@ -816,6 +837,7 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (
       h->loop_cycles = (unsigned long long)(clock64() - cycles0);
       h->loop_ticks = (unsigned long long)(wall_clock64() - ticks0);
     }
+
     const int rx2 = fresh(rx), ry2 = fresh(ry);
     double lu[TH], lv[TW];
 #pragma unroll
