@@ -54,9 +54,9 @@ def useful_ops_per_entry_iter(M: int, fp32: bool) -> float:
 # branch; cross-lane ds_swizzle and LDS accesses issue on another pipeline and are not counted).  Keyed by
 # (M, small tiles).
 LOOP_VALU_PER_WAVE_ITER = {
-    (4, False): (116, 1024), (4, True): (38, 256), (8, False): (108, 1024), (8, True): (42, 256),
-    (16, False): (180, 2048), (16, True): (100, 1024), (32, False): (166, 2048), (32, True): (112, 1024),
-    (64, False): (386, 4096),
+    (4, False): (108, 1024), (4, True): (36, 256), (8, False): (104, 1024), (8, True): (40, 256),
+    (16, False): (176, 2048), (16, True): (98, 1024), (32, False): (164, 2048), (32, True): (110, 1024),
+    (64, False): (384, 4096),
 }
 # a matrix with fewer blocks than this runs the small-tile instantiation (the library's own choice, mirrored here
 # only to pick the row of the table above)
