@@ -60,7 +60,8 @@ LOOP_VALU_PER_WAVE_ITER = {
 }
 # a matrix with fewer blocks than this runs the small-tile instantiation (the library's own choice, mirrored here
 # only to pick the row of the table above)
-SMALL_TILES_BELOW_BLOCKS = {4: 50000, 8: 9000, 16: 9000, 32: 1500, 64: 0}
+SMALL_TILES_BELOW_BLOCKS = {False: {4: 100000, 8: 13000, 16: 40000, 32: 3200, 64: 0},     # default mode
+                            True: {4: 55000, 8: 12000, 16: 9000, 32: 2100, 64: 0}}         # with the fp32 flag
 
 
 def recorded_traffic(workload: str, fp32: bool):
@@ -234,7 +235,7 @@ def bench_matrix(args, name):
     steps = args.steps
     fp32_flag = binding.TSENOR_FLAG_FP32_ITERATIONS
     # a matrix this small runs on the small tiles, which iterate in double whatever the flag says
-    small_launch = nblocks < SMALL_TILES_BELOW_BLOCKS[w.M]
+    small_launch = nblocks < SMALL_TILES_BELOW_BLOCKS[True][w.M]
     headline_fp32 = args.precision == "fp32" and not small_launch
     no_cpu, no_modes = args.no_cpu_baseline, args.no_other_modes
     if args.tol > 0.0:
@@ -312,7 +313,7 @@ def bench_matrix(args, name):
             roofline["pass_traffic_over_algorithmic"] = round(
                 traffic["pass"] / roofline["algorithmic_bytes_per_pass"], 2)
         if not fp32 and w.iters > 0:
-            small = nblocks < SMALL_TILES_BELOW_BLOCKS[w.M]
+            small = nblocks < SMALL_TILES_BELOW_BLOCKS[False][w.M]
             counted = LOOP_VALU_PER_WAVE_ITER.get((w.M, small))
             if counted:
                 # second view of the same measurement: the vector instructions the loop issues against the issue

@@ -105,7 +105,8 @@ enum {
    * TSENOR_FLAG_SIMPLE_ROUNDING; ignored otherwise): 16 entries per lane (4 for M <= 8),
    * more lanes per block, a shorter dependent chain per iteration: best while the launch cannot fill the
    * chip anyway; on them the whole path, Algorithm 2 included, runs in one kernel (the TSENOR_FLAG_GREEDY_* choice
-   * does not apply).  Default: chosen by the number of blocks of the matrix.  Setting both is an error. */
+   * does not apply).  Default: chosen by the number of blocks of the matrix (and earlier for the large tiles when
+   * TSENOR_FLAG_FP32_ITERATIONS is set, which only they honour).  Setting both is an error. */
   TSENOR_FLAG_TILES_LARGE = 1u << 5,
   TSENOR_FLAG_TILES_SMALL = 1u << 6,
   /* Ablation arm "Simple" of App. B.2.1 in place of Algorithm 2: per block, keep the N largest plan entries

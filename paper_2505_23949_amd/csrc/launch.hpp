@@ -23,12 +23,18 @@ struct Variant {
   }
 };
 
-// Below this many blocks in a matrix the Dykstra kernel uses the small tiles (M <= 32, double iterations):
-// with so few waves every SIMD holds at most one, whose iteration time is its instruction count.
-// Measured crossovers (300 iterations of a few blocks, small against large tiles: M = 32: 108 us against 140;
-// M = 16: 91 against 146; M = 8: 46 against 84; M = 4: 35 against 90).
-constexpr int64_t small_tiles_below_blocks(int M) {
-  return M == 4 ? 50000 : M == 8 ? 9000 : M == 16 ? 9000 : M == 32 ? 1500 : 0;
+// Below this many blocks in a matrix the whole path runs in the one kernel with the small tiles (M <= 32, double
+// iterations): with few waves a SIMD holds one or two, whose iteration time is the dependent chain, and the
+// rounding needs no launches of its own.  `fp32`: the caller asked for single-precision iterations, which only
+// the large tiles have, so they win earlier.  Measured crossovers of a whole call, T = 300 (ms, small / large
+// fp64 / large fp32): M = 32: 3072 blocks 0.259 / 0.280 / 0.216, 3328 blocks 0.314 / 0.286 / 0.222, 2048 blocks
+// 0.189 / 0.198 / 0.188; M = 16: 8192 blocks 0.165 / 0.202 / 0.182, 9216 blocks 0.209 / 0.258 / 0.196, 32 768
+// blocks 0.484 / 0.492 / 0.367, 65 536 blocks 0.916 / 0.886 / 0.567; M = 8: 12 288 blocks 0.102 / 0.104 / 0.101,
+// 16 384 blocks 0.128 / 0.107 / 0.102; M = 4: 49 152 blocks 0.085 / 0.104 / 0.095, 57 344 blocks 0.107 / 0.106 /
+// 0.097, 81 920 blocks 0.133 / 0.174 / 0.113, 131 072 blocks 0.199 / 0.186 / 0.126.
+constexpr int64_t small_tiles_below_blocks(int M, bool fp32) {
+  return M == 4 ? (fp32 ? 55000 : 100000) : M == 8 ? (fp32 ? 12000 : 13000) : M == 16 ? (fp32 ? 9000 : 40000)
+       : M == 32 ? (fp32 ? 2100 : 3200) : 0;
 }
 
 // Below this many blocks in a launch the greedy selection runs with M lanes per block: the one-lane kernel

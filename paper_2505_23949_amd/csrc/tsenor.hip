@@ -207,11 +207,12 @@ inline Variant variant_of(const tsenor_problem& p) {
   // the tiling is decided from the matrix's own number of blocks, never from what it is fused with: the two
   // tilings differ in the order of the additions inside a row or column sum
   const int64_t nblocks = (p.rows / p.M) * (p.cols / p.M);
+  const bool fp32 = (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0;
   v.small = p.M <= 32 && !v.zero_t && !v.simple &&
             ((p.flags & TSENOR_FLAG_TILES_SMALL) != 0 ||
-             (!(p.flags & TSENOR_FLAG_TILES_LARGE) && nblocks < small_tiles_below_blocks(p.M)));
+             (!(p.flags & TSENOR_FLAG_TILES_LARGE) && nblocks < small_tiles_below_blocks(p.M, fp32)));
   // the small tiles (launches that cannot fill the chip: bound by latency, not by issue) iterate in double only
-  v.fast = p.iters > 0 && (p.flags & TSENOR_FLAG_FP32_ITERATIONS) != 0 && !v.small;
+  v.fast = p.iters > 0 && fp32 && !v.small;
   v.adaptive = p.tol > 0.0 && p.iters > 0;
   return v;
 }
