@@ -361,6 +361,14 @@ __device__ __forceinline__ float mul_clamp01(float x, float y) {
   return r;
 }
 
+// max(a, b) as the bare instruction: fmaxf() first quiets a possible signalling NaN in an operand the compiler
+// has not just computed (the loop-invariant floor below), one more instruction in every iteration
+__device__ __forceinline__ float max_as_is(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
 // The same iteration in single precision.  kap stays as rebuilt (no rounding accumulates in it); the scalings
 // U (every tile row) and V (every tile column) are kept as numbers, and the capped entry is
 //     e_ij = clamp(kap_ij * (U_i V_j)):  a multiply, a multiply with the clamp modifier, the add of the row
@@ -423,7 +431,7 @@ __device__ __forceinline__ float dykstra_iteration_f32(const float (&kap)[TH][TW
   reduce_scatter_y<T, float, TW>(C);
 #pragma unroll
   for (int b = 0; b < OWN_C; ++b) {
-    C[b] = Nf * fast_rcp(fmaxf(C[b], Nf * 0x1p-10f));
+    C[b] = Nf * fast_rcp(max_as_is(C[b], Nf * 0x1p-10f));
     if constexpr (ADAPT) {
       worst = fmaxf(worst, fabsf(C[b] - 1.0f));
       C[b] = frozen ? 1.0f : C[b];
@@ -817,11 +825,13 @@ __global__ __launch_bounds__((DykstraLaunch<M, FAST, ADAPT, SMALL>::kThreads), (
           } else {
             for (; t < stop; ++t) dykstra_iteration_f32<T, kLdsGather32>(kap32, U32, V32, Nf, xr, rx);
           }
+          // (the scalings of the rows and columns this lane owns: every row and column has its owner, and the
+          // other copies of a scaling are the same number)
           float mxs = U32[0], mns = U32[0];
 #pragma unroll
-          for (int a = 1; a < TH; ++a) mxs = fmaxf(mxs, U32[a]), mns = fminf(mns, U32[a]);
+          for (int a = 1; a < OWN_R; ++a) mxs = fmaxf(mxs, U32[a]), mns = fminf(mns, U32[a]);
 #pragma unroll
-          for (int b = 0; b < TW; ++b) mxs = fmaxf(mxs, V32[b]), mns = fminf(mns, V32[b]);
+          for (int b = 0; b < OWN_C; ++b) mxs = fmaxf(mxs, V32[b]), mns = fminf(mns, V32[b]);
           // wave-uniform: fold the fp32 scalings into the double ones when any lane's have drifted
           if (t < p.T && __any(!(mxs < hi && mns > lo))) {
             fold();
