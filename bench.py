@@ -145,12 +145,14 @@ def bench_layer(args):
     for _ in range(args.warmup):
         binding.tsenor_mask_batched(probs, work)
     ms_per_step, ms_events = timed_calls(torch, lambda: binding.tsenor_mask_batched(probs, work), args.steps)
+    ms_median, ms_min = per_pass_ms(torch, lambda: binding.tsenor_mask_batched(probs, work), max(args.steps, 10))
     weights = sum(w.rows * w.cols for w in ws)
     return {
         "metric": "masked weights/s (Dykstra+rounding), 16:32, one 8B decoder layer per batched call",
         "value": round(weights / (ms_per_step * 1e-3), 1), "unit": "masked weights/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "ms_per_step_hip_events": round(ms_events, 4), "higher_is_better": True,
+        "ms_per_step_hip_events": round(ms_events, 4), "ms_per_step_median": round(ms_median, 4),
+        "ms_per_step_min": round(ms_min, 4), "trials": max(args.steps, 10), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if args.precision == "fp32" else "f64",
         "data": "synthetic",
         "config": {"workload": "cfg4_layer", "matrices": [[w.rows, w.cols] for w in ws], "weights": weights,
@@ -195,12 +197,14 @@ def bench_slab_loop(args):
         one_pass()
     steps = max(args.steps // 4, 1)
     ms_per_step, ms_events = timed_calls(torch, one_pass, steps)
+    ms_median, ms_min = per_pass_ms(torch, one_pass, 10)
     weights = w.rows * w.cols
     return {
         "metric": f"masked weights/s, {w.N}:{w.M}, {nslabs} dependent calls of a {w.rows}x{w.M} slab",
         "value": round(weights / (ms_per_step * 1e-3), 1), "unit": "masked weights/s", "n_gpus": 1,
         "steps": steps, "warmup": max(args.warmup // 2, 1), "ms_per_step": round(ms_per_step, 4),
-        "ms_per_step_hip_events": round(ms_events, 4), "ms_per_call": round(ms_per_step / nslabs, 5),
+        "ms_per_step_hip_events": round(ms_events, 4), "ms_per_step_median": round(ms_median, 4),
+        "ms_per_step_min": round(ms_min, 4), "trials": 10, "ms_per_call": round(ms_per_step / nslabs, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "slab_loop", "rows": w.rows, "cols": w.cols, "N": w.N, "M": w.M, "iters": w.iters,
                    "tau": w.tau, "tau_mode": "rel_matrix_max (per slab)", "storage": w.dtype, "importance": w.dist,
