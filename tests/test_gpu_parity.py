@@ -18,6 +18,9 @@ pytestmark = pytest.mark.gpu
 
 PLAN_ATOL = 1e-9
 FP32_PLAN_ATOL = 1e-4      # bar for the fp32-iteration mode (see the tests of that mode below)
+# two plan entries of a block whose log-keys are closer than this (relative) count as tied in the randomised test:
+# 100 times the ~1e-12 to which the two sides agree on a key after thousands of operations
+TIE_REL_GAP = 1e-10
 
 
 @pytest.fixture(scope="module")
@@ -384,7 +387,7 @@ def test_randomised_configurations(dev):
         keys = np.sort(exact.blocks(ref["log_S"], M).reshape(-1, M * M), axis=1)
         gap = np.diff(keys, axis=1)
         scale = np.maximum(np.abs(keys[:, 1:]), np.abs(keys[:, :-1]))
-        close = gap <= 1e-9 * np.maximum(scale, 1e-3)
+        close = gap <= TIE_REL_GAP * np.maximum(scale, 1e-3)
         if iters == 0:
             close &= gap > 0        # equal importances give equal keys on both sides: index order on both
         else:
@@ -412,7 +415,7 @@ def test_randomised_configurations(dev):
             compared_blocks += tied.size
             tied_blocks += int(tied.sum())
         print(f"  tied blocks left out of the exact comparison: {int(tied.sum())} of {tied.size}", flush=True)
-    # With the default seed: 4 of 407 (0 to 2.4 % over twenty other seeds), all four in one draw whose squared, column-scaled importance has one column
+    # With the default seed: 4 of 407 (0 to 1.7 % over a dozen other seeds of 64 draws), all four in one draw whose squared, column-scaled importance has one column
     # that outweighs every other entry of its rows by more than e^40: after the row projection those entries
     # equal log N to the last bit in every row, a tie in exact arithmetic as far as doubles can tell.
     print(f"[summary] tied blocks over all draws: {tied_blocks} of {compared_blocks}", flush=True)
