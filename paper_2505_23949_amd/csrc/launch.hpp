@@ -38,11 +38,13 @@ constexpr int64_t small_tiles_below_blocks(int M, bool fp32) {
 }
 
 // Below this many blocks in a launch the greedy selection runs with M lanes per block: the one-lane kernel
-// takes the time of M*M dependent steps of a single wave however few blocks there are (22 / 70 / 300 us for
-// M = 16 / 32 / 64), the M-lane kernel issues several times the instructions but its chain is M steps
-// (14 / 23 / 41 us), so it wins while it does not fill the chip.  Measured crossovers; for M <= 8 the
+// takes the time of M*M dependent steps of a single wave however few blocks there are (22 / 70 / 310 us for
+// M = 16 / 32 / 64), the M-lane kernel issues several times the instructions but its chain is M steps, so it
+// wins while it does not fill the chip.  Measured crossovers (us, one lane / M lanes, T = 300): M = 32: 8192
+// blocks 70 / 52, 12 288 blocks 70 / 69, 16 384 blocks 70 / 84; M = 16: 12 288 blocks 22 / 20, 16 384 blocks
+// 23 / 25; M = 64: 8192 blocks 308 / 214, 12 288 blocks 317 / 315, 16 384 blocks 314 / 396.  For M <= 8 the
 // one-lane kernel is never slower.
-constexpr int64_t greedy_wide_below_blocks(int M) { return M == 16 ? 2500 : M == 32 ? 7000 : M == 64 ? 16000 : 0; }
+constexpr int64_t greedy_wide_below_blocks(int M) { return M == 16 ? 14000 : M == 32 ? 12000 : M == 64 ? 12000 : 0; }
 
 // Enqueues the kernels of one fused launch that depend on M: tile load + Algorithm 1 + sort, greedy selection
 // (or the simple rounding arm), local search + mask write.  `b.count` non-degenerate problems of variant v.
