@@ -69,7 +69,8 @@ bool launch_block_kernels(Batch& b, const Variant& v, hipStream_t stream, hipEve
     greedy_wide_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
   } else {
     if (!assign_groups(b, kWave)) return false;
-    greedy_kernel<M><<<b.first[b.count], kWave, 0, stream>>>(b);
+    constexpr int GW = kGreedyWaves<M>;
+    greedy_kernel<M><<<(b.first[b.count] + GW - 1) / GW, kWave * GW, 0, stream>>>(b);
   }
   if (ev_greedy) (void)hipEventRecord(ev_greedy, stream);
   if (!assign_groups(b, kWave / M)) return false;

@@ -20,6 +20,14 @@ __device__ __forceinline__ int mask_popc(mask_t v) {
     return __popc((unsigned int)v);
 }
 
+// Waves per workgroup of greedy_kernel.  A full matrix gives the kernel about one wave per SIMD (57 344 blocks: 896
+// waves for 1024 SIMDs), and a wave's pace is its own dependent chain: it must not share a SIMD while others
+// idle.  One-wave workgroups were placed unevenly (0.096 ms for the headline matrix); workgroups of four waves, one
+// per SIMD of a CU, take 0.077 ms.  (M = 64 keeps one wave: its 36 KB of LDS per wave already spread the
+// workgroups, and four waves measured the same.)  The waves of a workgroup do not interact.
+template <int M>
+constexpr int kGreedyWaves = M <= 32 ? 4 : 1;
+
 // Algorithm 2 lines 1-6: scan the entries of a block in sorted order and keep an entry while its row
 // and its column hold fewer than N.  The chain of M*M dependent steps runs with ONE LANE PER BLOCK, so
 // every lane of the wave does useful work; the state of a lane (M row masks, M column counters) lives in
@@ -27,19 +35,24 @@ __device__ __forceinline__ int mask_popc(mask_t v) {
 // entry), not by memory: the scan order is prefetched a cache line ahead and the LDS state of four entries
 // is fetched per round trip.  Output: the mask as M row bit masks per block (bit c of word r = S[r][c]).
 template <int M>
-__global__ __launch_bounds__(kWave) void greedy_kernel(Batch batch) {
+__global__ __launch_bounds__(kWave * kGreedyWaves<M>) void greedy_kernel(Batch batch) {
   using mask_t = block_mask_t<M>;
   constexpr int MM = M * M;
-  __shared__ mask_t rowbits[M][kWave];
-  __shared__ unsigned char colcnt[M][kWave];
-  const int which = find_problem(batch, blockIdx.x);
+  __shared__ mask_t rowbits_[kGreedyWaves<M>][M][kWave];
+  __shared__ unsigned char colcnt_[kGreedyWaves<M>][M][kWave];
+  auto& rowbits = rowbits_[threadIdx.x / kWave];
+  auto& colcnt = colcnt_[threadIdx.x / kWave];
+  // `vgroup` counts 64-block groups across the launch, as the group prefix of the batch does
+  const unsigned int vgroup = blockIdx.x * kGreedyWaves<M> + threadIdx.x / kWave;
+  if (vgroup >= batch.first[batch.count]) return;  // (a whole wave; the kernel has no barrier)
+  const int which = find_problem(batch, vgroup);
   const unsigned short* order = batch.e[which].order;
   const int64_t nblocks = batch.e[which].p.nblocks;
   const int N = batch.e[which].p.N;
   mask_t* rowmask = static_cast<mask_t*>(batch.e[which].rowmask);
   WsHeader* hdr = batch.e[which].hdr;
-  const int lane = threadIdx.x;
-  const int64_t blk = (int64_t)(blockIdx.x - batch.first[which]) * kWave + lane;
+  const int lane = threadIdx.x % kWave;
+  const int64_t blk = (int64_t)(vgroup - batch.first[which]) * kWave + lane;
   for (int k = 0; k < M; ++k) {
     rowbits[k][lane] = 0;
     colcnt[k][lane] = 0;
