@@ -546,10 +546,13 @@ struct DykstraLaunch {
   static constexpr int kWavesPerGroup = (ADAPT || SMALL) ? 1 : 4;
   static constexpr int kThreads = kWavesPerGroup * kWave;
   // waves per SIMD the register budget is set for.  The fp32 loop wants more than two (one wave issues at
-  // most every ~5 cycles, an fp32 instruction occupies the SIMD for 2); the kernel needs 158 registers, which
-  // fits three waves (168 each) without spills; four waves (128, a few spills outside the loop) measured the
-  // same.  The double-precision loop holds twice the state: two waves of up to 256 registers.
-  static constexpr int kWavesPerSimd = (FAST && M <= 32) ? 3 : 2;
+  // most every ~5 cycles, an fp32 instruction occupies the SIMD for 2-3): three waves of 168 registers.  For
+  // M <= 32 the whole kernel fits them without spills (four waves, 128 registers and a few spills outside the
+  // loop, measured the same).  For M = 64 the loop fits (64 + 64 registers for the tile and the capped entries)
+  // but the double-precision phases around it do not (the warm-up iterations on a tile of 64 doubles, the sort
+  // of 64 keys): they spill ~90 registers to scratch, none inside the loop, and the kernel is 5.5 % faster than
+  // with two waves.  The double-precision loop holds twice the state: two waves of up to 256 registers.
+  static constexpr int kWavesPerSimd = FAST ? 3 : 2;
 };
 
 // ZERO_T: the instantiation for T = 0 (no iterations, keys are K itself).  It is a template parameter
