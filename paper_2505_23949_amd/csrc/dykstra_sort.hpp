@@ -551,8 +551,10 @@ struct DykstraLaunch {
   // loop, measured the same).  For M = 64 the loop fits (64 + 64 registers for the tile and the capped entries)
   // but the double-precision phases around it do not (the warm-up iterations on a tile of 64 doubles, the sort
   // of 64 keys): they spill ~90 registers to scratch, none inside the loop, and the kernel is 5.5 % faster than
-  // with two waves.  The double-precision loop holds twice the state: two waves of up to 256 registers.
-  static constexpr int kWavesPerSimd = FAST ? 3 : 2;
+  // with two waves (not with the early exit, where a block may run a dozen iterations and the code around the loop
+  // is most of the work: two waves there).  The double-precision loop holds twice the state: two waves of up to
+  // 256 registers.
+  static constexpr int kWavesPerSimd = FAST && !(M == 64 && ADAPT) ? 3 : 2;
 };
 
 // ZERO_T: the instantiation for T = 0 (no iterations, keys are K itself).  It is a template parameter
