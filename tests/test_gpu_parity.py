@@ -226,6 +226,26 @@ def test_both_greedy_kernels_give_the_sequential_selection(dev, M, N):
             assert np.array_equal(res["stats"].cpu().numpy(), full["stats"]), (name, levels)
 
 
+@pytest.mark.parametrize("M,N,block_rows,block_cols", [(16, 8, 10, 33), (32, 16, 3, 43), (8, 3, 9, 50), (64, 32, 2, 35)])
+def test_one_lane_greedy_with_a_ragged_last_workgroup(dev, M, N, block_rows, block_cols):
+    # the one-lane greedy kernel runs in workgroups of four waves (64 blocks per wave) for M <= 32: block counts
+    # that leave the last workgroup with idle waves and the last wave with idle lanes
+    import torch
+
+    from paper_2505_23949_amd import binding
+
+    w = synth.Workload(f"ragged_greedy_{N}of{M}", block_rows * M, block_cols * M, N, M, 0.01, 25, "f32", "wanda", 4300 + M)
+    g = synth.generate(w)
+    W, cs = _to_device(g, w, dev)
+    print(f"[case] one-lane greedy, {block_rows * block_cols} blocks of {N}:{M}", flush=True)
+    res = binding.solve(W, N, M, w.tau, w.iters, col_scale=cs, tau_mode=w.tau_mode, want_stats=True,
+                        flags=binding.TSENOR_FLAG_GREEDY_ONE_LANE | binding.TSENOR_FLAG_TILES_LARGE)
+    torch.cuda.synchronize()
+    ref = oracle.mask(g["W_f32"], N, M, w.tau, w.iters, col_scale=g["col_scale"], tau_mode=w.tau_mode)
+    assert np.array_equal(res["mask"].cpu().numpy(), ref["mask"])
+    assert np.array_equal(res["stats"].cpu().numpy(), ref["stats"])
+
+
 @pytest.mark.parametrize("M,N", [(4, 2), (4, 1), (8, 3), (16, 8), (32, 16), (64, 32), (64, 5)])
 def test_simple_rounding_arm_is_its_definition(dev, M, N):
     # TSENOR_FLAG_SIMPLE_ROUNDING (App. B.2.1: row-wise then column-wise N:M rounding) for every block size,
