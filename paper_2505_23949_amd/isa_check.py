@@ -11,8 +11,10 @@ numbers silently:
 
 `hazards()` scans an ISA listing for both, with a hand-written instruction on the reading side (H1) or the
 writing side (H2).  Hand-written instructions are recognised by how they are printed: without the encoding suffix
-the compiler gives its own (`v_min_f32` against `v_min_f32_e32`), or as the one form written with it
-(`v_mul_f32_e64 ... clamp`).  `listing()` compiles one translation unit to such a listing.
+the compiler gives its own 32-bit ones (`v_min_f32` against `v_min_f32_e32`), or as the one form written with it
+(`v_mul_f32_e64 ... clamp`).  The 64-bit minimum and maximum print without a suffix whoever wrote them; all of
+them are treated as hand-written, which only makes the check stricter.  `listing()` compiles one translation
+unit to such a listing.
 """
 from __future__ import annotations
 
